@@ -1,0 +1,188 @@
+"""Patch-stage benchmark: one step = one pf_stage_patch_forward call (all rows of the hot path) on one patch of
+a synthetic workload, inputs resident in HBM.  Prints ONE JSON line (tokens/s, ms per step, roofline of the
+dominant kernel, CPU-oracle baseline).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu]
+
+Only one GPU is used; --gpus N with N > 1 exits with a message.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def flops_per_launch(cfg, cls, rows):
+    """Algorithmic flops of one launch of a kernel class on `rows` query/GEMM rows (2mnk per GEMM, 4 n Lkv d for
+    attention's two contractions)."""
+    d, F, Lkv = cfg["hidden"], cfg["mlp_dim"], wl.kv_rows(cfg)
+    if cls == "attention":
+        return 4.0 * rows * Lkv * d
+    if cls == "xattn":
+        return 4.0 * rows * cfg["text_len"] * d
+    if cls == "gemm_qkv":
+        return 2.0 * rows * 3 * d * d
+    if cls in ("gemm_out", "gemm_xattn"):
+        return 2.0 * rows * d * d
+    if cls == "gemm_up":
+        return 2.0 * rows * F * d
+    if cls == "gemm_down":
+        return 2.0 * rows * d * (F + (d if cfg["kind"] == 3 else 0))
+    return 0.0
+
+
+def call_flops(cfg, rows):
+    """Algorithmic flops of one patch call on `rows` rows (image-only call: rows = n)."""
+    d, F, Lkv, nl = cfg["hidden"], cfg["mlp_dim"], wl.kv_rows(cfg), cfg["n_layers"]
+    per_tok = 2 * d * 3 * d + 4 * Lkv * d + 2 * d * d + 4 * d * F
+    if cfg["kind"] == 1:
+        per_tok += 4 * d * d + 4 * cfg["text_len"] * d
+    return float(per_tok) * rows * nl
+
+
+def bytes_per_launch(cfg, cls, rows):
+    """Algorithmic HBM bytes of one launch of a streaming kernel class."""
+    d = cfg["hidden"]
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    if cls == "ln_modulate":
+        return rows * d * (4 + esz)           # fp32 residual row in, dtype row out
+    if cls == "kv_scatter":
+        return 2 * 2 * rows * d * esz         # k and v rows read and written once
+    return 0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--path", type=int, default=0, help="0 auto (MFMA for bf16), 1 force SIMT kernels")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the multi-GPU pipeline schedule is out of scope); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2405_14430_amd import Stage
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = wl.CONFIGS[args.workload]
+    n, M = wl.patch_rows(cfg), cfg["n_patches"]
+    W, A = wl.make_weights(cfg), wl.make_activations(cfg)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    dt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    cond = dev(A["cond"])
+    text = None
+    if A["text"] is not None:
+        text = dev(A["text"]).to(dt) if cfg["kind"] == 1 else dev(A["text"])
+    st = Stage(cfg, W)
+    st.kv_init(dev(A["x_prev"]), cond, text)
+    x = dev(A["x"])
+    xs = [x[p * n:(p + 1) * n].contiguous() for p in range(M)]
+    ys = [torch.empty_like(t) for t in xs]
+    torch.cuda.synchronize()
+
+    def step(i):
+        p = i % M
+        st.patch_forward(xs[p], cond, p, out=ys[p])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = n / (ms_per_step * 1e-3)
+    tflops = call_flops(cfg, n) / (ms_per_step * 1e-3) / 1e12
+
+    # second pass, same steps, with HIP event pairs around every launch on the stage's stream
+    st.profile(1)
+    for i in range(args.steps):
+        step(i)
+    prof = st.profile_read()
+    st.profile(0)
+    kernels = {}
+    for cls, (ms, cnt) in prof.items():
+        if cnt:
+            kernels[cls] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
+                            "avg_us": ms / cnt * 1e3}
+    flop_classes = [c for c in kernels if flops_per_launch(cfg, c, n) > 0]
+    dom = max(flop_classes, key=lambda c: kernels[c]["ms_per_step"])
+    peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_F32_TFLOPS
+    for c in kernels:
+        f = flops_per_launch(cfg, c, n)
+        b = bytes_per_launch(cfg, c, n)
+        if f:
+            kernels[c]["tflops"] = f / (kernels[c]["avg_us"] * 1e-6) / 1e12
+        if b:
+            kernels[c]["gbs"] = b / (kernels[c]["avg_us"] * 1e-6) / 1e9
+    ach = kernels[dom]["tflops"]
+    roofline = {"kernel": dom, "bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "achieved": ach, "peak": peak,
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                "avg_launch_us": kernels[dom]["avg_us"],
+                "flops_per_launch": flops_per_launch(cfg, dom, n)}
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle.pf_oracle import StageOracle
+        orc = StageOracle(cfg, W)
+        if cfg["kind"] == 1:
+            orc.kv_init(None, text=A["text"])
+        for l in range(cfg["n_layers"]):
+            k, v = wl.make_kv_fill(cfg, l)
+            orc.set_kv(l, k, v)
+        calls, tc0 = 0, time.perf_counter()
+        while True:
+            orc.patch_forward(A["x"][calls % M * n:(calls % M + 1) * n], A["cond"], calls % M)
+            calls += 1
+            if time.perf_counter() - tc0 > 10.0 or calls >= 8:
+                break
+        tc = time.perf_counter() - tc0
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        except Exception:
+            threads = os.cpu_count()
+        cpu = {"value": calls * n / tc, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+               "sample": f"{calls} patch_forward call(s) of {args.workload} (n={n} tokens each) on synthetic stale K/V, "
+                         f"numpy float64, {tc:.1f} s"}
+
+    out = {
+        "metric": "patch-stage tokens/s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "kind": cfg["kind"], "n_layers": cfg["n_layers"], "hidden": cfg["hidden"],
+                   "heads": cfg["n_heads"], "head_dim": cfg["head_dim"], "mlp_dim": cfg["mlp_dim"],
+                   "seq_img": cfg["seq_img"], "n_patches": M, "patch_tokens": n, "kv_rows": wl.kv_rows(cfg),
+                   "text_len": cfg["text_len"]},
+        "tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,316 @@
+// Streaming (HBM-bound) kernels of the patch stage: modulation vectors, LayerNorm + adaLN modulate,
+// the K/V scatter into the full-sequence buffers (PipeFusion Sec. 3.3: fresh rows of the current patch
+// replace the stale ones before attention), the split-KV combine, and a zero fill.
+#include "common.h"
+#include "ops.h"
+
+namespace pf {
+
+// ------------------------------------------------------------------------------------------------
+// modulation: mod = W * SiLU(c) + b   (one wave per output), or mod = table + c
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void modulation_kernel(const T *__restrict__ w, const T *__restrict__ b,
+                                                         const float *__restrict__ c, float *__restrict__ mod,
+                                                         int out_dim, int in_dim, int table_mode) {
+  if (table_mode) {
+    int j = blockIdx.x * 256 + threadIdx.x;
+    if (j < out_dim) mod[j] = to_f32(w[j]) + c[j];
+    return;
+  }
+  extern __shared__ float sc[];  // SiLU(c), in_dim floats
+  for (int i = threadIdx.x; i < in_dim; i += 256) sc[i] = silu_f(c[i]);
+  __syncthreads();
+  constexpr int V = Vec16<T>::N;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // 8 outputs per wave, 32 per block
+  for (int o = 0; o < 8; ++o) {
+    int j = blockIdx.x * 32 + wave * 8 + o;
+    if (j >= out_dim) break;
+    const T *row = w + (size_t)j * in_dim;
+    float acc = 0.f;
+    for (int i = lane * V; i < in_dim; i += 64 * V) {
+      float v[V];
+      Vec16<T>::load(row + i, v);
+#pragma unroll
+      for (int t = 0; t < V; ++t) acc = fmaf(v[t], sc[i + t], acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) mod[j] = acc + to_f32(b[j]);
+  }
+}
+
+hipError_t launch_modulation(int dt, const void *w, const void *b, const float *c, float *mod, int out_dim,
+                             int in_dim, int table_mode, hipStream_t s) {
+  if (table_mode) {
+    dim3 g((out_dim + 255) / 256);
+    if (dt == DT_BF16)
+      modulation_kernel<bf16_t><<<g, 256, 0, s>>>((const bf16_t *)w, nullptr, c, mod, out_dim, in_dim, 1);
+    else
+      modulation_kernel<float><<<g, 256, 0, s>>>((const float *)w, nullptr, c, mod, out_dim, in_dim, 1);
+  } else {
+    dim3 g((out_dim + 31) / 32);
+    size_t sh = (size_t)in_dim * sizeof(float);
+    if (dt == DT_BF16)
+      modulation_kernel<bf16_t><<<g, 256, sh, s>>>((const bf16_t *)w, (const bf16_t *)b, c, mod, out_dim, in_dim, 0);
+    else
+      modulation_kernel<float><<<g, 256, sh, s>>>((const float *)w, (const float *)b, c, mod, out_dim, in_dim, 0);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// LayerNorm + modulate: one wave per row, the row lives in registers (single pass over HBM).
+// NC = float4 chunks per lane; d <= NC * 256.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void ln_modulate_kernel(const float *__restrict__ x, int64_t ldx,
+                                                          const float *__restrict__ shift,
+                                                          const float *__restrict__ scale, float eps,
+                                                          T *__restrict__ out, int64_t ldo, int rows, int d,
+                                                          int normalize) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float *xr = x + (size_t)row * ldx;
+  float4 v[NC];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    int c = (lane + 64 * i) * 4;
+    if (c < d) {
+      v[i] = *reinterpret_cast<const float4 *>(xr + c);
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    } else {
+      v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  float mean = 0.f, rstd = 1.f;
+  if (normalize) {
+    mean = wave_sum(sum) / (float)d;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      int c = (lane + 64 * i) * 4;
+      if (c < d) {
+        float a = v[i].x - mean, b = v[i].y - mean, e = v[i].z - mean, f = v[i].w - mean;
+        sq += (a * a + b * b) + (e * e + f * f);
+      }
+    }
+    rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+  }
+  T *orow = out + (size_t)row * ldo;
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    int c = (lane + 64 * i) * 4;
+    if (c < d) {
+      float y[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+      if (normalize) {
+        float4 sh = *reinterpret_cast<const float4 *>(shift + c);
+        float4 sc = *reinterpret_cast<const float4 *>(scale + c);
+        y[0] = (y[0] - mean) * rstd * (1.f + sc.x) + sh.x;
+        y[1] = (y[1] - mean) * rstd * (1.f + sc.y) + sh.y;
+        y[2] = (y[2] - mean) * rstd * (1.f + sc.z) + sh.z;
+        y[3] = (y[3] - mean) * rstd * (1.f + sc.w) + sh.w;
+      }
+      if constexpr (sizeof(T) == 4) {
+        *reinterpret_cast<float4 *>(orow + c) = make_float4(y[0], y[1], y[2], y[3]);
+      } else {
+        bf16x4 o;
+        o[0] = (bf16_t)y[0]; o[1] = (bf16_t)y[1]; o[2] = (bf16_t)y[2]; o[3] = (bf16_t)y[3];
+        *reinterpret_cast<bf16x4 *>(orow + c) = o;
+      }
+    }
+  }
+}
+
+template <typename T, int NC>
+static void ln_launch(const float *x, int64_t ldx, const float *shift, const float *scale, float eps, void *out,
+                      int64_t ldo, int rows, int d, int normalize, hipStream_t s) {
+  ln_modulate_kernel<T, NC><<<dim3((rows + 3) / 4), 256, 0, s>>>(x, ldx, shift, scale, eps, (T *)out, ldo, rows, d,
+                                                                normalize);
+}
+
+template <typename T>
+static hipError_t ln_dispatch(const float *x, int64_t ldx, const float *shift, const float *scale, float eps,
+                              void *out, int64_t ldo, int rows, int d, int normalize, hipStream_t s) {
+  int need = (d + 255) / 256;
+#define PF_LN_CASE(NC) \
+  if (need <= NC) { ln_launch<T, NC>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, s); return hipGetLastError(); }
+  PF_LN_CASE(2) PF_LN_CASE(4) PF_LN_CASE(5) PF_LN_CASE(6) PF_LN_CASE(8) PF_LN_CASE(12) PF_LN_CASE(16) PF_LN_CASE(32)
+#undef PF_LN_CASE
+  return hipErrorInvalidValue;  // d > 8192 is rejected by the caller
+}
+
+hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *shift, const float *scale,
+                              float eps, void *out, int64_t ldo, int rows, int d, int normalize, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  return dt == DT_BF16 ? ln_dispatch<bf16_t>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, s)
+                       : ln_dispatch<float>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// K/V scatter (+ optional RoPE on q and k).
+//   blocks [0, nbk): one thread per 16-byte chunk of the q and k parts of a row.  k chunks are copied to
+//     K[h][row0+i][c..]; with rope both q and k chunks are rotated, written back in place, and the rotated
+//     k goes to the buffer.
+//   blocks [nbk, nbk+nbv): 64x64 (rows x channels) tiles of v transposed through LDS into V^T[h][c][row0+i].
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void kv_scatter_kernel(T *__restrict__ qkv, int64_t ld, T *__restrict__ kbuf,
+                                                         T *__restrict__ vtbuf, int Lp, int H, int dh, int row0,
+                                                         int rows, int rope, int tok0, int grid_w, float theta,
+                                                         int nbk) {
+  constexpr int V = Vec16<T>::N;
+  const int d = H * dh;
+  if ((int)blockIdx.x < nbk) {
+    const int cpr = d / V;  // chunks per row per part
+    const int parts = rope ? 2 : 1;
+    int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)rows * parts * cpr) return;
+    int i = (int)(id / (parts * cpr));
+    int rem = (int)(id % (parts * cpr));
+    int part = rope ? rem / cpr : 1;  // 0 = q, 1 = k
+    int ch = (rem % cpr) * V;         // channel within the part
+    T *src = qkv + (size_t)i * ld + (size_t)part * d + ch;
+    float v[V];
+    Vec16<T>::load(src, v);
+    int h = ch / dh, c = ch % dh;
+    if (rope && tok0 >= 0) {
+      int tok = tok0 + i;
+      float pr = (float)(tok / grid_w), pc = (float)(tok % grid_w);
+      int quarter = dh / 4;  // pairs per axis
+#pragma unroll
+      for (int t = 0; t < V; t += 2) {
+        int j = (c + t) >> 1;  // pair index within the head
+        int ia = j < quarter ? j : j - quarter;
+        float pos = j < quarter ? pr : pc;
+        // frequency theta^(-2*ia / (dh/2))
+        float freq = exp2f(-log2f(theta) * (4.0f * (float)ia / (float)dh));
+        float sn, cs;
+        sincosf(pos * freq, &sn, &cs);
+        float a = v[t], b = v[t + 1];
+        v[t] = a * cs - b * sn;
+        v[t + 1] = a * sn + b * cs;
+      }
+    }
+    if (rope) {
+      Vec16<T>::store(src, v);   // rotated (or, for text rows, unchanged) values stay in qkv
+      Vec16<T>::load(src, v);    // what reaches the buffer is exactly what qkv now holds
+    }
+    if (part == 1) {
+      T *dst = kbuf + ((size_t)h * Lp + (row0 + i)) * dh + c;
+      if (rope) {
+        Vec16<T>::store(dst, v);
+      } else {
+        *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
+      }
+    }
+    return;
+  }
+  // ---- V transpose tiles
+  __shared__ T tile[64][64 + 2];
+  const int bid = blockIdx.x - nbk;
+  const int ctiles = (d + 63) / 64;
+  const int r0 = (bid / ctiles) * 64, c0 = (bid % ctiles) * 64;
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+    int r = e >> 6, c = e & 63;
+    if (r0 + r < rows && c0 + c < d) tile[r][c] = qkv[(size_t)(r0 + r) * ld + 2 * (size_t)d + c0 + c];
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+    int c = e >> 6, r = e & 63;
+    if (r0 + r < rows && c0 + c < d) {
+      int ch = c0 + c;
+      int h = ch / dh, cc = ch % dh;
+      vtbuf[((size_t)h * dh + cc) * Lp + row0 + r0 + r] = tile[r][c];
+    }
+  }
+}
+
+hipError_t launch_kv_scatter(const ScatterArgs &a, hipStream_t s) {
+  if (a.rows <= 0) return hipSuccess;
+  const int d = a.n_heads * a.head_dim;
+  const int V = a.dt == DT_BF16 ? 8 : 4;
+  int64_t kthreads = (int64_t)a.rows * (a.rope ? 2 : 1) * (d / V);
+  int nbk = (int)((kthreads + 255) / 256);
+  int nbv = ((a.rows + 63) / 64) * ((d + 63) / 64);
+  dim3 g(nbk + nbv);
+  if (a.dt == DT_BF16)
+    kv_scatter_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t *)a.qkv, a.ld, (bf16_t *)a.kbuf, (bf16_t *)a.vtbuf,
+                                                a.rows_padded, a.n_heads, a.head_dim, a.row0, a.rows, a.rope,
+                                                a.tok0, a.grid_w, a.theta, nbk);
+  else
+    kv_scatter_kernel<float><<<g, 256, 0, s>>>((float *)a.qkv, a.ld, (float *)a.kbuf, (float *)a.vtbuf,
+                                               a.rows_padded, a.n_heads, a.head_dim, a.row0, a.rows, a.rope, a.tok0,
+                                               a.grid_w, a.theta, nbk);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// split-KV combine: partial (unnormalised O, running max m, running sum l) per split -> normalised output.
+// ws layout: O[splits][nq][H*dh] floats, then ml[splits][nq][H][2].
+// ------------------------------------------------------------------------------------------------
+size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
+  if (splits <= 1) return 0;
+  size_t o = (size_t)splits * nq * n_heads * head_dim;
+  size_t ml = (size_t)splits * nq * n_heads * 2;
+  return (o + ml) * sizeof(float);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, T *__restrict__ out,
+                                                           int64_t ldo, int nq, int H, int dh, int splits) {
+  const int d = H * dh;
+  const int cpr = d / 4;
+  int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (int64_t)nq * cpr) return;
+  int i = (int)(id / cpr), ch = (int)(id % cpr) * 4;
+  int h = ch / dh;
+  const float *ml = ws + (size_t)splits * nq * d;
+  float M = -INFINITY;
+  for (int sidx = 0; sidx < splits; ++sidx) M = fmaxf(M, ml[(((size_t)sidx * nq + i) * H + h) * 2]);
+  float L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int sidx = 0; sidx < splits; ++sidx) {
+    const float *p = ml + (((size_t)sidx * nq + i) * H + h) * 2;
+    float m = p[0], l = p[1];
+    if (l <= 0.f) continue;  // split saw no key
+    float wgt = expf(m - M);
+    L += l * wgt;
+    float4 v = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
+    o[0] += v.x * wgt; o[1] += v.y * wgt; o[2] += v.z * wgt; o[3] += v.w * wgt;
+  }
+  float inv = 1.f / L;
+  T *dst = out + (size_t)i * ldo + ch;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) Elem<T>::store(dst + t, o[t] * inv);
+}
+
+hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s) {
+  const int d = a.n_heads * a.head_dim;
+  int64_t threads = (int64_t)a.nq * (d / 4);
+  dim3 g((unsigned)((threads + 255) / 256));
+  if (a.dt == DT_BF16)
+    attn_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads, a.head_dim, a.splits);
+  else
+    attn_combine_kernel<float><<<g, 256, 0, s>>>(a.ws, (float *)a.out, a.ldo, a.nq, a.n_heads, a.head_dim, a.splits);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4 *p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  size_t n16 = bytes / 16;
+  unsigned blocks = (unsigned)((n16 + 255) / 256);
+  if (blocks > 8192) blocks = 8192;
+  fill_zero_kernel<<<dim3(blocks), 256, 0, s>>>((uint4 *)p, n16);
+  return hipGetLastError();
+}
+
+}  // namespace pf

@@ -1,0 +1,40 @@
+// GEMM epilogues shared by the SIMT and MFMA GEMM kernels.
+//   mode 0: C[row][col] (dtype) = acc + bias[col], GELU on columns >= gelu_from
+//   mode 1: X[row][col] (fp32)  = R[row][col] + gate[col] * (acc + bias[col]); optional rounded copy in C2
+#pragma once
+#include "common.h"
+
+namespace pf {
+
+template <typename T>
+struct Epilogue {
+  const T *bias;
+  void *C; int64_t ldc;
+  int mode, gelu_from, gelu_tanh;
+  const float *gate;
+  const float *R; int64_t ldr;
+  T *C2; int64_t ldc2;
+
+  __device__ __forceinline__ void apply(int row, int col, float acc) const {
+    float v = acc + (bias ? to_f32(bias[col]) : 0.f);
+    if (mode == 0) {
+      if (col >= gelu_from) v = gelu_f(v, gelu_tanh);
+      Elem<T>::store(reinterpret_cast<T *>(C) + (size_t)row * ldc + col, v);
+    } else {
+      float g = gate ? gate[col] : 1.f;
+      float x = R[(size_t)row * ldr + col] + g * v;
+      reinterpret_cast<float *>(C)[(size_t)row * ldc + col] = x;
+      if (C2) Elem<T>::store(C2 + (size_t)row * ldc2 + col, x);
+    }
+  }
+};
+
+template <typename T, typename Args>
+inline Epilogue<T> make_epilogue(const Args &a) {
+  Epilogue<T> e;
+  e.bias = (const T *)a.bias; e.C = a.C; e.ldc = a.ldc; e.mode = a.epilogue; e.gelu_from = a.gelu_from;
+  e.gelu_tanh = a.gelu_tanh; e.gate = a.gate; e.R = a.R; e.ldr = a.ldr; e.C2 = (T *)a.C2; e.ldc2 = a.ldc2;
+  return e;
+}
+
+}  // namespace pf

@@ -1,0 +1,68 @@
+// Internal launch interface between the stage runtime (stage.cpp) and the kernel files.
+// Every function only enqueues work on `s` and returns the launch status; shapes are validated
+// by the callers (the C-ABI layer) before these are reached.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pf {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { PATH_AUTO = 0, PATH_SIMT = 1 };
+
+inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+hipError_t launch_modulation(int dt, const void *w, const void *b, const float *c, float *mod, int out_dim,
+                             int in_dim, int table_mode, hipStream_t s);
+
+hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *shift, const float *scale,
+                              float eps, void *out, int64_t ldo, int rows, int d, int normalize,
+                              hipStream_t s);
+
+struct GemmArgs {
+  int dt, path;
+  const void *A; int64_t lda;
+  const void *W; int64_t ldw;
+  const void *bias;
+  void *C; int64_t ldc;
+  int M, N, K;
+  int epilogue;        // 0: store dtype (+GELU from column gelu_from); 1: fp32 residual update
+  int gelu_from, gelu_tanh;
+  const float *gate;   // [N] or nullptr
+  const float *R; int64_t ldr;
+  void *C2; int64_t ldc2;
+};
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+
+struct ScatterArgs {
+  int dt;
+  void *qkv; int64_t ld;
+  void *kbuf, *vtbuf;
+  int rows_padded, n_heads, head_dim, row0, rows;
+  int rope, tok0, grid_w; float theta;
+};
+hipError_t launch_kv_scatter(const ScatterArgs &a, hipStream_t s);
+
+struct AttnArgs {
+  int dt, path;
+  const void *q; int64_t ldq;
+  const void *kbuf, *vtbuf;
+  int kv_rows, rows_padded, n_heads, head_dim;
+  void *out; int64_t ldo;
+  int nq, splits;
+  float *ws;           // partial results when splits > 1
+};
+size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits);
+hipError_t launch_attention(const AttnArgs &a, hipStream_t s, bool *used_combine);
+
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);   // bytes multiple of 16, p 16-byte aligned
+
+// kernel-path specific pieces (defined in gemm_*.hip / attn_*.hip)
+hipError_t launch_gemm_simt(const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);
+hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);
+
+}  // namespace pf

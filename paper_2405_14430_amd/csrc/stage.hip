@@ -1,0 +1,562 @@
+// Stage runtime and C boundary (include/pfstage.h): configuration checks, carving of the caller's K/V buffer
+// and workspace, and the per-layer launch sequence of one PipeFusion stage pass (Sec. 3.3) for the four block
+// kinds.  Host code only; every arithmetic step runs in the kernels of the other files.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/pfstage.h"
+#include "ops.h"
+
+using namespace pf;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Derived {
+  int n, T, Tj, Lkv, Lp, Tp, Rmax, mod_chunks, n_streams;
+  size_t esz;
+};
+
+bool is_joint(int kind) { return kind == PF_BLOCK_MMDIT_JOINT || kind == PF_BLOCK_SINGLE_STREAM; }
+
+const char *check_config(const pf_config *c, pf_status *st) {
+  *st = PF_ERR_CONFIG;
+  if (c->dtype != PF_F32 && c->dtype != PF_BF16) { *st = PF_ERR_DTYPE; return "unknown dtype"; }
+  if (c->kind < 0 || c->kind > 3) return "unknown block kind";
+  if (c->kernel_path != PF_PATH_AUTO && c->kernel_path != PF_PATH_SIMT) return "unknown kernel_path";
+  if (c->n_layers < 1) return "n_layers must be >= 1";
+  if (c->hidden < 8 || c->n_heads < 1 || c->head_dim < 8) return "hidden/n_heads/head_dim too small";
+  if (c->hidden != c->n_heads * c->head_dim) return "hidden != n_heads * head_dim";
+  if (c->head_dim % 8 || c->head_dim > 128) return "head_dim must be a multiple of 8 and <= 128";
+  if (c->hidden > 8192) return "hidden must be <= 8192";
+  if (c->mlp_dim < 8 || c->mlp_dim % 8) return "mlp_dim must be a positive multiple of 8";
+  if (c->seq_img < 1 || c->n_patches < 1 || c->seq_img % c->n_patches) return "n_patches must divide seq_img";
+  if (c->grid_h < 1 || c->grid_w < 1 || (int64_t)c->grid_h * c->grid_w != c->seq_img) return "grid_h * grid_w != seq_img";
+  if (c->text_len < 0) return "text_len < 0";
+  if (c->kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
+    if (c->text_len < 1) return "kind 1 needs text_len >= 1";
+    if (c->cross_dim < 8 || c->cross_dim % 8) return "cross_dim must be a positive multiple of 8";
+  }
+  if (c->kind == PF_BLOCK_ADALN_ZERO && c->text_len != 0) return "kind 0 has no text";
+  if (!(c->ln_eps > 0.f)) return "ln_eps must be > 0";
+  if (c->kind == PF_BLOCK_SINGLE_STREAM && !(c->rope_theta > 1.f)) return "rope_theta must be > 1";
+  *st = PF_OK;
+  return nullptr;
+}
+
+Derived derive(const pf_config *c) {
+  Derived d;
+  d.n = c->seq_img / c->n_patches;
+  d.T = c->text_len;
+  d.Tj = is_joint(c->kind) ? c->text_len : 0;
+  d.Lkv = c->seq_img + d.Tj;
+  d.Lp = (int)align_up(d.Lkv, 128);
+  d.Tp = (int)align_up(d.T > 0 ? d.T : 1, 128);
+  d.Rmax = d.Lkv;
+  d.mod_chunks = c->kind == PF_BLOCK_SINGLE_STREAM ? 3 : 6;
+  d.n_streams = c->kind == PF_BLOCK_MMDIT_JOINT ? 2 : 1;
+  d.esz = dt_size(c->dtype);
+  return d;
+}
+
+int use_path(const pf_config *c) { return (c->dtype == PF_BF16 && c->kernel_path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT; }
+
+// Split of the key range so that a launch has about two workgroups per compute unit.
+int choose_splits(int path, int nq, int H, int kv_rows) {
+  const int qtile = path == PATH_SIMT ? 64 : 128;
+  const int ktile = path == PATH_SIMT ? 32 : 64;
+  int64_t blocks = (int64_t)((nq + qtile - 1) / qtile) * H;
+  int tiles = (kv_rows + ktile - 1) / ktile;
+  int want = (int)((512 + blocks - 1) / blocks);
+  int cap = tiles / 4;  // at least four tiles per split
+  if (want > cap) want = cap;
+  if (want > 16) want = 16;
+  return want < 1 ? 1 : want;
+}
+
+size_t kv_layer_bytes(const pf_config *c, const Derived &d) {
+  size_t self = 2 * (size_t)c->n_heads * d.Lp * c->head_dim * d.esz;
+  size_t cross = c->kind == PF_BLOCK_ADALN_SINGLE_XATTN ? 2 * (size_t)c->n_heads * d.Tp * c->head_dim * d.esz : 0;
+  return self + cross;
+}
+
+struct WsLayout {
+  size_t mod, xres, h, qkv, a, u, xb, qc, attn, total;
+  size_t attn_bytes;
+  int64_t lda_a;  // row stride of the attention-output buffer (d, or d+F for kind 3)
+};
+
+WsLayout ws_layout(const pf_config *c, const Derived &d) {
+  WsLayout w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  const size_t R = d.Rmax, D = c->hidden, F = c->mlp_dim, e = d.esz;
+  w.mod = take((size_t)d.n_streams * c->n_layers * d.mod_chunks * D * sizeof(float));
+  w.xres = take(R * D * sizeof(float));
+  w.h = take(R * D * e);
+  w.qkv = take(R * 3 * D * e);
+  if (c->kind == PF_BLOCK_SINGLE_STREAM) {
+    w.lda_a = D + F;
+    w.a = take(R * (D + F) * e);
+    w.u = w.a;
+  } else {
+    w.lda_a = D;
+    w.a = take(R * D * e);
+    w.u = take(R * F * e);
+  }
+  if (c->kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
+    w.xb = take(R * D * e);
+    w.qc = take(R * D * e);
+  }
+  const int path = use_path(c);
+  size_t ab = 0;
+  int shapes[2] = {d.n + d.Tj, d.Rmax};
+  for (int nq : shapes) {
+    size_t b = attention_ws_bytes(nq, c->n_heads, c->head_dim, choose_splits(path, nq, c->n_heads, d.Lkv));
+    if (b > ab) ab = b;
+    if (c->kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
+      b = attention_ws_bytes(nq, c->n_heads, c->head_dim, choose_splits(path, nq, c->n_heads, d.T));
+      if (b > ab) ab = b;
+    }
+  }
+  w.attn_bytes = ab;
+  w.attn = take(ab);
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+struct pf_stage {
+  pf_config cfg;
+  Derived d;
+  WsLayout w;
+  std::vector<pf_layer_weights> img, txt;
+  char *kv;
+  char *ws;
+  hipStream_t stream;
+  bool ready = false;
+  std::string err;
+  // profiling
+  bool prof = false;
+  struct Ev { int cls; hipEvent_t a, b; };
+  std::vector<Ev> events;
+  std::vector<hipEvent_t> pool;
+
+  char *kptr(int l) const { return kv + (size_t)l * kv_layer_bytes(&cfg, d); }
+  char *vptr(int l) const { return kptr(l) + (size_t)cfg.n_heads * d.Lp * cfg.head_dim * d.esz; }
+  char *kcptr(int l) const { return kptr(l) + 2 * (size_t)cfg.n_heads * d.Lp * cfg.head_dim * d.esz; }
+  char *vcptr(int l) const { return kcptr(l) + (size_t)cfg.n_heads * d.Tp * cfg.head_dim * d.esz; }
+  float *mod(int stream_idx, int l) const {
+    return (float *)(ws + w.mod) + ((size_t)stream_idx * cfg.n_layers + l) * d.mod_chunks * cfg.hidden;
+  }
+};
+
+namespace {
+
+pf_status fail(pf_stage *s, pf_status st, const std::string &msg) {
+  if (s) s->err = msg; else g_create_error = msg;
+  return st;
+}
+
+hipEvent_t get_event(pf_stage *s) {
+  if (!s->pool.empty()) { hipEvent_t e = s->pool.back(); s->pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+// Runs one launch, optionally bracketed by an event pair for the per-class timing.
+template <typename Fn>
+hipError_t run(pf_stage *s, int cls, Fn &&fn) {
+  if (!s->prof) return fn();
+  pf_stage::Ev ev{cls, get_event(s), get_event(s)};
+  (void)hipEventRecord(ev.a, s->stream);
+  hipError_t e = fn();
+  (void)hipEventRecord(ev.b, s->stream);
+  s->events.push_back(ev);
+  return e;
+}
+
+#define PF_TRY(expr)                                                                       \
+  do {                                                                                     \
+    hipError_t e__ = (expr);                                                               \
+    if (e__ != hipSuccess)                                                                 \
+      return fail(s, PF_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e__));   \
+  } while (0)
+
+hipError_t gemm(pf_stage *s, int cls, const void *A, int64_t lda, const void *W, int64_t ldw, const void *bias,
+                void *C, int64_t ldc, int M, int N, int K, int epilogue, int gelu_from, const float *gate,
+                const float *R, int64_t ldr, void *C2, int64_t ldc2) {
+  GemmArgs g{};
+  g.dt = s->cfg.dtype; g.path = use_path(&s->cfg);
+  g.A = A; g.lda = lda; g.W = W; g.ldw = ldw; g.bias = bias; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
+  g.epilogue = epilogue; g.gelu_from = gelu_from; g.gelu_tanh = s->cfg.gelu_tanh; g.gate = gate; g.R = R; g.ldr = ldr;
+  g.C2 = C2; g.ldc2 = ldc2;
+  return run(s, cls, [&] { return launch_gemm(g, s->stream); });
+}
+
+hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const void *kb, const void *vb, int kv_rows,
+                     int rows_padded, void *out, int64_t ldo, int nq) {
+  AttnArgs a{};
+  a.dt = s->cfg.dtype; a.path = use_path(&s->cfg);
+  a.q = q; a.ldq = ldq; a.kbuf = kb; a.vtbuf = vb; a.kv_rows = kv_rows; a.rows_padded = rows_padded;
+  a.n_heads = s->cfg.n_heads; a.head_dim = s->cfg.head_dim; a.out = out; a.ldo = ldo; a.nq = nq;
+  a.splits = choose_splits(a.path, nq, a.n_heads, kv_rows);
+  a.ws = (float *)(s->ws + s->w.attn);
+  hipError_t e = run(s, cls, [&] { return a.path == PATH_SIMT ? launch_attn_simt(a, s->stream) : launch_attn_mfma(a, s->stream); });
+  if (e != hipSuccess) return e;
+  if (a.splits > 1) e = run(s, PF_KC_ATTN_COMBINE, [&] { return launch_attn_combine(a, s->stream); });
+  return e;
+}
+
+// The block stack on image rows [img_off, img_off + n_img) and, for the joint kinds, on the T text rows when
+// `text` is given.  Residual rows live in the workspace, text rows first.
+pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const float *cond, const float *text,
+                  float *y_img, float *text_out) {
+  const pf_config &c = s->cfg;
+  const Derived &d = s->d;
+  const WsLayout &w = s->w;
+  const int D = c.hidden, F = c.mlp_dim, dt = c.dtype;
+  const size_t e = d.esz;
+  const int Tt = (text && d.Tj) ? d.Tj : 0;   // text rows processed by this call
+  const int R = Tt + n_img;
+  hipStream_t st = s->stream;
+  char *ws = s->ws;
+  float *xres = (float *)(ws + w.xres);
+  char *h = ws + w.h, *qkv = ws + w.qkv, *a = ws + w.a, *u = ws + w.u;
+
+  if (Tt) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres, text, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres + (size_t)Tt * D, x_img, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+
+  // a0: modulation vectors of every layer (and stream)
+  for (int l = 0; l < c.n_layers; ++l) {
+    for (int si = 0; si < d.n_streams; ++si) {
+      if (c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt) continue;   // text stream idle
+      const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
+      const int out_dim = d.mod_chunks * D;
+      const int table = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
+      PF_TRY(run(s, PF_KC_MODULATION, [&] { return launch_modulation(dt, lw.w_mod, lw.b_mod, cond, s->mod(si, l), out_dim, D, table, st); }));
+    }
+  }
+
+  const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
+  for (int l = 0; l < c.n_layers; ++l) {
+    char *kb = s->kptr(l), *vb = s->vptr(l);
+    if (c.kind == PF_BLOCK_SINGLE_STREAM) {
+      const pf_layer_weights &lw = s->img[l];
+      const float *m = s->mod(0, l);
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xres, D, m, m + D, c.ln_eps, h, D, R, D, 1, st); }));
+      PF_TRY(gemm(s, PF_KC_GEMM_QKV, h, D, lw.w_qkv, D, lw.b_qkv, qkv, 3 * D, R, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0, nullptr, 0));
+      // MLP branch runs in parallel with attention: GELU(h W_up^T + b) lands right of the attention columns
+      PF_TRY(gemm(s, PF_KC_GEMM_UP, h, D, lw.w_up, D, lw.b_up, a + (size_t)D * e, D + F, R, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
+      ScatterArgs sa{dt, qkv, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, 0, Tt, 1, -1, c.grid_w, c.rope_theta};
+      if (Tt) PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+      sa.qkv = qkv + (size_t)Tt * 3 * D * e; sa.row0 = row0_img; sa.rows = n_img; sa.tok0 = img_off;
+      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+      PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D + F, R));
+      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xres, D, R, D, D + F, 1, 0, m + 2 * D, xres, D, nullptr, 0));
+      continue;
+    }
+
+    // kinds 0, 1, 2: streams = [text (kind 2, if present), image]
+    struct Stream { const pf_layer_weights *lw; const float *m; int r0, nr, brow0; };
+    Stream streams[2];
+    int ns = 0;
+    if (c.kind == PF_BLOCK_MMDIT_JOINT && Tt) streams[ns++] = Stream{&s->txt[l], s->mod(0, l), 0, Tt, 0};
+    streams[ns++] = Stream{&s->img[l], s->mod(d.n_streams - 1, l), Tt, n_img, row0_img};
+
+    for (int si = 0; si < ns; ++si) {
+      const Stream &sm = streams[si];
+      const float *xs = xres + (size_t)sm.r0 * D;
+      char *hs = h + (size_t)sm.r0 * D * e;
+      char *qs = qkv + (size_t)sm.r0 * 3 * D * e;
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, sm.nr, D, 1, st); }));
+      PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, sm.lw->w_qkv, D, sm.lw->b_qkv, qs, 3 * D, sm.nr, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0, nullptr, 0));
+      ScatterArgs sa{dt, qs, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, sm.brow0, sm.nr, 0, -1, c.grid_w, c.rope_theta};
+      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+    }
+    PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R));
+    for (int si = 0; si < ns; ++si) {
+      const Stream &sm = streams[si];
+      float *xs = xres + (size_t)sm.r0 * D;
+      char *hs = h + (size_t)sm.r0 * D * e;
+      char *as = a + (size_t)sm.r0 * D * e;
+      char *us = u + (size_t)sm.r0 * F * e;
+      const bool xattn = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
+      char *xb = xattn ? ws + w.xb : nullptr;
+      PF_TRY(gemm(s, PF_KC_GEMM_OUT, as, D, sm.lw->w_o, D, sm.lw->b_o, xs, D, sm.nr, D, D, 1, 0, sm.m + 2 * D, xs, D, xb, D));
+      if (xattn) {
+        char *qc = ws + w.qc;
+        PF_TRY(gemm(s, PF_KC_GEMM_XATTN, xb, D, sm.lw->xattn_wq, D, sm.lw->xattn_bq, qc, D, sm.nr, D, D, 0, D, nullptr, nullptr, 0, nullptr, 0));
+        PF_TRY(attention(s, PF_KC_XATTN, qc, D, s->kcptr(l), s->vcptr(l), d.T, d.Tp, as, D, sm.nr));
+        PF_TRY(gemm(s, PF_KC_GEMM_XATTN, as, D, sm.lw->xattn_wo, D, sm.lw->xattn_bo, xs, D, sm.nr, D, D, 1, 0, nullptr, xs, D, nullptr, 0));
+      }
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m + 3 * D, sm.m + 4 * D, c.ln_eps, hs, D, sm.nr, D, 1, st); }));
+      PF_TRY(gemm(s, PF_KC_GEMM_UP, hs, D, sm.lw->w_up, D, sm.lw->b_up, us, F, sm.nr, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
+      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, us, F, sm.lw->w_down, F, sm.lw->b_down, xs, D, sm.nr, D, F, 1, 0, sm.m + 5 * D, xs, D, nullptr, 0));
+    }
+  }
+
+  if (y_img) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(y_img, xres + (size_t)Tt * D, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  if (Tt && text_out) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(text_out, xres, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  return PF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pf_stage_kv_bytes(const pf_config *cfg) {
+  pf_status st;
+  if (!cfg || check_config(cfg, &st)) return 0;
+  Derived d = derive(cfg);
+  return kv_layer_bytes(cfg, d) * cfg->n_layers;
+}
+
+size_t pf_stage_workspace_bytes(const pf_config *cfg) {
+  pf_status st;
+  if (!cfg || check_config(cfg, &st)) return 0;
+  Derived d = derive(cfg);
+  return ws_layout(cfg, d).total;
+}
+
+pf_status pf_stage_create(const pf_config *cfg, const pf_layer_weights *layers, void *kv_buffer, size_t kv_bytes,
+                          void *workspace, size_t ws_bytes, void *hip_stream, pf_stage **out) {
+  if (out) *out = nullptr;
+  if (!cfg || !layers || !kv_buffer || !workspace || !out) return fail(nullptr, PF_ERR_NULL, "null argument to pf_stage_create");
+  pf_status st;
+  if (const char *msg = check_config(cfg, &st)) return fail(nullptr, st, msg);
+  Derived d = derive(cfg);
+  WsLayout w = ws_layout(cfg, d);
+  if (kv_bytes < kv_layer_bytes(cfg, d) * cfg->n_layers) return fail(nullptr, PF_ERR_WORKSPACE, "kv buffer too small");
+  if (ws_bytes < w.total) return fail(nullptr, PF_ERR_WORKSPACE, "workspace too small");
+  if (((uintptr_t)kv_buffer & 255) || ((uintptr_t)workspace & 255)) return fail(nullptr, PF_ERR_WORKSPACE, "kv buffer and workspace must be 256-byte aligned");
+  const int kind = cfg->kind;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const pf_layer_weights *streams[2] = {&layers[l], kind == PF_BLOCK_MMDIT_JOINT ? layers[l].txt : nullptr};
+    if (kind == PF_BLOCK_MMDIT_JOINT && !layers[l].txt) return fail(nullptr, PF_ERR_NULL, "kind 2 needs text-stream weights (txt)");
+    for (const pf_layer_weights *lw : streams) {
+      if (!lw) continue;
+      bool ok = lw->w_mod && lw->w_qkv && lw->b_qkv && lw->w_up && lw->b_up && lw->w_down && lw->b_down;
+      if (kind != PF_BLOCK_ADALN_SINGLE_XATTN) ok = ok && lw->b_mod;
+      if (kind != PF_BLOCK_SINGLE_STREAM) ok = ok && lw->w_o && lw->b_o;
+      if (kind == PF_BLOCK_ADALN_SINGLE_XATTN)
+        ok = ok && lw->xattn_wq && lw->xattn_bq && lw->xattn_wkv && lw->xattn_bkv && lw->xattn_wo && lw->xattn_bo;
+      if (!ok) return fail(nullptr, PF_ERR_NULL, "a required weight pointer of layer " + std::to_string(l) + " is null");
+    }
+  }
+  pf_stage *s = new pf_stage();
+  s->cfg = *cfg; s->d = d; s->w = w;
+  s->img.assign(layers, layers + cfg->n_layers);
+  if (kind == PF_BLOCK_MMDIT_JOINT)
+    for (int l = 0; l < cfg->n_layers; ++l) s->txt.push_back(*layers[l].txt);
+  s->kv = (char *)kv_buffer; s->ws = (char *)workspace; s->stream = (hipStream_t)hip_stream;
+  *out = s;
+  g_create_error.clear();
+  return PF_OK;
+}
+
+pf_status pf_kv_init(pf_stage *s, const float *x_prev, const pf_cond *cp, float *y_prev) {
+  if (!s) return PF_ERR_NULL;
+  const pf_config &c = s->cfg;
+  const Derived &d = s->d;
+  if (c.kind == PF_BLOCK_ADALN_SINGLE_XATTN && (!cp || !cp->text)) return fail(s, PF_ERR_NULL, "kind 1: pf_kv_init needs cond_prev->text");
+  if (x_prev) {
+    if (!cp || !cp->cond) return fail(s, PF_ERR_NULL, "warm-up pass needs cond_prev->cond");
+    if (d.Tj && !cp->text) return fail(s, PF_ERR_NULL, "joint kinds: warm-up pass needs cond_prev->text");
+  }
+  s->err.clear();
+  PF_TRY(run(s, PF_KC_COPY, [&] { return launch_fill_zero(s->kv, kv_layer_bytes(&c, d) * c.n_layers, s->stream); }));
+  if (c.kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
+    // text keys/values of every layer's cross-attention, computed once
+    const int D = c.hidden;
+    char *qkv = s->ws + s->w.qkv;
+    for (int l = 0; l < c.n_layers; ++l) {
+      const pf_layer_weights &lw = s->img[l];
+      PF_TRY(gemm(s, PF_KC_GEMM_XATTN, cp->text, c.cross_dim, lw.xattn_wkv, c.cross_dim, lw.xattn_bkv, qkv + (size_t)D * d.esz,
+                  3 * D, d.T, 2 * D, c.cross_dim, 0, 2 * D, nullptr, nullptr, 0, nullptr, 0));
+      ScatterArgs sa{c.dtype, qkv, 3 * D, s->kcptr(l), s->vcptr(l), d.Tp, c.n_heads, c.head_dim, 0, d.T, 0, -1, c.grid_w, c.rope_theta};
+      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, s->stream); }));
+    }
+  }
+  if (x_prev) {
+    pf_status st = forward(s, x_prev, c.seq_img, 0, cp->cond, d.Tj ? (const float *)cp->text : nullptr, y_prev,
+                           d.Tj ? cp->text_out : nullptr);
+    if (st != PF_OK) return st;
+  }
+  s->ready = true;
+  return PF_OK;
+}
+
+pf_status pf_stage_patch_forward(pf_stage *s, const float *x_patch, const pf_cond *cond, int patch_idx, float *y_patch) {
+  if (!s) return PF_ERR_NULL;
+  if (!x_patch || !y_patch || !cond || !cond->cond) return fail(s, PF_ERR_NULL, "null argument to pf_stage_patch_forward");
+  if (!s->ready) return fail(s, PF_ERR_STATE, "pf_kv_init must run before pf_stage_patch_forward");
+  if (patch_idx < 0 || patch_idx >= s->cfg.n_patches) return fail(s, PF_ERR_RANGE, "patch index out of range");
+  const bool joint_text = s->d.Tj && cond->text;
+  if (joint_text && !cond->text_out) return fail(s, PF_ERR_NULL, "text rows given without text_out");
+  s->err.clear();
+  return forward(s, x_patch, s->d.n, patch_idx * s->d.n, cond->cond, joint_text ? (const float *)cond->text : nullptr,
+                 y_patch, joint_text ? cond->text_out : nullptr);
+}
+
+static pf_status fill_view(const pf_stage *s, int layer, bool cross, pf_kv_view_t *out) {
+  if (!s || !out) return PF_ERR_NULL;
+  if (layer < 0 || layer >= s->cfg.n_layers) return PF_ERR_RANGE;
+  if (cross && s->cfg.kind != PF_BLOCK_ADALN_SINGLE_XATTN) return PF_ERR_CONFIG;
+  const int dh = s->cfg.head_dim;
+  const int rp = cross ? s->d.Tp : s->d.Lp;
+  out->k = cross ? s->kcptr(layer) : s->kptr(layer);
+  out->v = cross ? s->vcptr(layer) : s->vptr(layer);
+  out->rows = cross ? s->d.T : s->d.Lkv;
+  out->rows_padded = rp;
+  out->text_rows = cross ? 0 : s->d.Tj;
+  out->elem_bytes = (int32_t)s->d.esz;
+  out->k_row_stride = dh; out->k_head_stride = (int64_t)rp * dh; out->k_col_stride = 1;
+  out->v_row_stride = 1; out->v_head_stride = (int64_t)dh * rp; out->v_col_stride = rp;
+  return PF_OK;
+}
+
+pf_status pf_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, false, out); }
+pf_status pf_xattn_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, true, out); }
+
+pf_status pf_stage_set_stream(pf_stage *s, void *hip_stream) {
+  if (!s) return PF_ERR_NULL;
+  s->stream = (hipStream_t)hip_stream;
+  return PF_OK;
+}
+
+pf_status pf_stage_profile(pf_stage *s, int enable) {
+  if (!s) return PF_ERR_NULL;
+  s->prof = enable != 0;
+  return PF_OK;
+}
+
+pf_status pf_stage_profile_read(pf_stage *s, double *ms, int64_t *launches) {
+  if (!s || !ms || !launches) return PF_ERR_NULL;
+  for (int i = 0; i < PF_KC_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  if (s->events.empty()) return PF_OK;
+  PF_TRY(hipStreamSynchronize(s->stream));
+  for (auto &ev : s->events) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, ev.a, ev.b) == hipSuccess) { ms[ev.cls] += t; launches[ev.cls] += 1; }
+    s->pool.push_back(ev.a);
+    s->pool.push_back(ev.b);
+  }
+  s->events.clear();
+  return PF_OK;
+}
+
+void pf_stage_destroy(pf_stage *s) {
+  if (!s) return;
+  for (auto &ev : s->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+  for (auto e : s->pool) (void)hipEventDestroy(e);
+  delete s;
+}
+
+const char *pf_status_str(pf_status st) {
+  switch (st) {
+    case PF_OK: return "PF_OK";
+    case PF_ERR_NULL: return "PF_ERR_NULL";
+    case PF_ERR_CONFIG: return "PF_ERR_CONFIG";
+    case PF_ERR_SHAPE: return "PF_ERR_SHAPE";
+    case PF_ERR_DTYPE: return "PF_ERR_DTYPE";
+    case PF_ERR_STATE: return "PF_ERR_STATE";
+    case PF_ERR_RANGE: return "PF_ERR_RANGE";
+    case PF_ERR_WORKSPACE: return "PF_ERR_WORKSPACE";
+    case PF_ERR_DEVICE: return "PF_ERR_DEVICE";
+  }
+  return "PF_ERR_UNKNOWN";
+}
+
+const char *pf_last_error(const pf_stage *s) { return s ? s->err.c_str() : g_create_error.c_str(); }
+
+// ---- single-operator entry points ---------------------------------------------------------------------------
+static bool dt_ok(int dt) { return dt == PF_F32 || dt == PF_BF16; }
+static bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+pf_status pf_op_modulation(int dtype, const void *w, const void *b, const float *c, float *mod, int out_dim, int in_dim,
+                           int table_mode, void *stream) {
+  if (!w || !c || !mod || (!table_mode && !b)) return PF_ERR_NULL;
+  if (!dt_ok(dtype)) return PF_ERR_DTYPE;
+  if (out_dim < 1 || in_dim < 8 || in_dim % 8 || in_dim > 12288 || !al16(w)) return PF_ERR_SHAPE;
+  return launch_modulation(dtype, w, b, c, mod, out_dim, in_dim, table_mode, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+pf_status pf_op_ln_modulate(int dtype, const float *x, int64_t ldx, const float *shift, const float *scale, float eps,
+                            void *out, int64_t ldo, int rows, int d, int normalize, void *stream) {
+  if (!x || !out || (normalize && (!shift || !scale))) return PF_ERR_NULL;
+  if (!dt_ok(dtype)) return PF_ERR_DTYPE;
+  if (rows < 0 || d < 8 || d % 8 || d > 8192 || ldx < d || ldo < d || ldx % 4 || ldo % 4 || !al16(x) || !al16(out)) return PF_ERR_SHAPE;
+  return launch_ln_modulate(dtype, x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void *W, int64_t ldw, const void *bias, void *C,
+                     int64_t ldc, int M, int N, int K, int epilogue, int gelu_from, int gelu_tanh, const float *gate,
+                     const float *R, int64_t ldr, void *C2, int64_t ldc2, void *stream) {
+  if (!A || !W || !C || (epilogue == 1 && !R)) return PF_ERR_NULL;
+  if (!dt_ok(dtype)) return PF_ERR_DTYPE;
+  if (M < 0 || N < 1 || K < 8 || K % 8 || lda < K || ldw < K || lda % 8 || ldw % 8 || ldc < N || !al16(A) || !al16(W)) return PF_ERR_SHAPE;
+  if (epilogue != 0 && epilogue != 1) return PF_ERR_SHAPE;
+  if (epilogue == 1 && ldr < N) return PF_ERR_SHAPE;
+  if (C2 && ldc2 < N) return PF_ERR_SHAPE;
+  GemmArgs g{};
+  g.dt = dtype; g.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT;
+  g.A = A; g.lda = lda; g.W = W; g.ldw = ldw; g.bias = bias; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
+  g.epilogue = epilogue; g.gelu_from = gelu_from; g.gelu_tanh = gelu_tanh; g.gate = gate; g.R = R; g.ldr = ldr; g.C2 = C2; g.ldc2 = ldc2;
+  return launch_gemm(g, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *vtbuf, int rows_padded, int n_heads,
+                           int head_dim, int row0, int rows, int rope, int tok0, int grid_w, float rope_theta, void *stream) {
+  if (!qkv || !kbuf || !vtbuf) return PF_ERR_NULL;
+  if (!dt_ok(dtype)) return PF_ERR_DTYPE;
+  const int64_t d = (int64_t)n_heads * head_dim;
+  if (n_heads < 1 || head_dim < 8 || head_dim % 8 || ld < 3 * d || ld % 8 || rows < 0 || row0 < 0 ||
+      (int64_t)row0 + rows > rows_padded || rows_padded % 8 || !al16(qkv) || !al16(kbuf) || !al16(vtbuf))
+    return PF_ERR_SHAPE;
+  if (rope && (head_dim % 4 || grid_w < 1 || !(rope_theta > 1.f))) return PF_ERR_SHAPE;
+  ScatterArgs sa{dtype, qkv, ld, kbuf, vtbuf, rows_padded, n_heads, head_dim, row0, rows, rope, tok0, grid_w, rope_theta};
+  return launch_kv_scatter(sa, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+size_t pf_op_attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
+  return attention_ws_bytes(nq, n_heads, head_dim, splits);
+}
+
+pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const void *kbuf, const void *vtbuf, int kv_rows,
+                          int rows_padded, int n_heads, int head_dim, void *out, int64_t ldo, int nq, int splits, void *ws,
+                          size_t ws_bytes, void *stream) {
+  if (!q || !kbuf || !vtbuf || !out) return PF_ERR_NULL;
+  if (!dt_ok(dtype)) return PF_ERR_DTYPE;
+  const int64_t d = (int64_t)n_heads * head_dim;
+  if (n_heads < 1 || head_dim < 8 || head_dim % 8 || head_dim > 128 || kv_rows < 1 || rows_padded % 128 || kv_rows > rows_padded ||
+      ldq < d || ldo < d || ldq % 8 || ldo % 4 || nq < 0 || splits < 1 || splits > 64 || !al16(q) || !al16(kbuf) || !al16(vtbuf) || ((uintptr_t)out & 7))
+    return PF_ERR_SHAPE;
+  if (splits > 1 && (!ws || ws_bytes < attention_ws_bytes(nq, n_heads, head_dim, splits) || !al16(ws))) return PF_ERR_WORKSPACE;
+  AttnArgs a{};
+  a.dt = dtype; a.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT;
+  a.q = q; a.ldq = ldq; a.kbuf = kbuf; a.vtbuf = vtbuf; a.kv_rows = kv_rows; a.rows_padded = rows_padded; a.n_heads = n_heads;
+  a.head_dim = head_dim; a.out = out; a.ldo = ldo; a.nq = nq; a.splits = splits; a.ws = (float *)ws;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = a.path == PATH_SIMT ? launch_attn_simt(a, st) : launch_attn_mfma(a, st);
+  if (e == hipSuccess && splits > 1) e = launch_attn_combine(a, st);
+  return e == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+}  // extern "C"
+
+namespace pf {
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s) {
+  return a.path == PATH_SIMT || a.dt != DT_BF16 ? launch_gemm_simt(a, s) : launch_gemm_mfma(a, s);
+}
+}  // namespace pf

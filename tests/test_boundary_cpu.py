@@ -1,0 +1,134 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every symbol the header
+declares, validates configurations and call order before anything would be launched, and sizes the K/V
+buffer as Sec. 3.4 (Table 1) says: full-sequence K and V for the stage's own layers."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import workloads as wl
+from paper_2405_14430_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2405_14430_amd.build import build
+        build()
+    return B.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "pfstage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(pf_[a-z_0-9]+)\s*\(", text))
+    assert {"pf_stage_create", "pf_kv_init", "pf_stage_patch_forward", "pf_kv_view"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+
+
+def test_kv_bytes_is_full_sequence_kv_for_own_layers(lib):
+    for name, cfg in wl.CONFIGS.items():
+        c = B.make_config(cfg)
+        esz = 2 if cfg["dtype"] == "bf16" else 4
+        Lp = (wl.kv_rows(cfg) + 127) // 128 * 128
+        per_layer = 2 * Lp * cfg["hidden"] * esz
+        if cfg["kind"] == 1:
+            per_layer += 2 * ((cfg["text_len"] + 127) // 128 * 128) * cfg["hidden"] * esz
+        assert lib.pf_stage_kv_bytes(C.byref(c)) == per_layer * cfg["n_layers"], name
+        # halving the layers of the stage halves the buffer: the (1/N)(KV)L entry of Table 1
+        if cfg["n_layers"] % 2 == 0:
+            c2 = B.make_config(cfg, n_layers=cfg["n_layers"] // 2)
+            assert lib.pf_stage_kv_bytes(C.byref(c2)) * 2 == lib.pf_stage_kv_bytes(C.byref(c))
+        assert lib.pf_stage_workspace_bytes(C.byref(c)) > 0
+
+
+BAD = [dict(hidden=100), dict(n_patches=7), dict(head_dim=12, n_heads=32), dict(dtype_code=5), dict(kind=9),
+       dict(grid_w=3), dict(mlp_dim=100), dict(n_layers=0), dict(ln_eps=0.0)]
+
+
+@pytest.mark.parametrize("bad", BAD)
+def test_invalid_configs_are_rejected(lib, bad):
+    cfg = dict(wl.CONFIGS["C1"])
+    code = bad.pop("dtype_code", None) if "dtype_code" in bad else None
+    cfg.update(bad)
+    c = B.make_config(cfg)
+    if code is not None:
+        c.dtype = code
+    assert lib.pf_stage_kv_bytes(C.byref(c)) == 0
+    kv = C.c_void_p(0x1000)
+    out = C.c_void_p()
+    layers = (B.PfLayerWeights * 1)()
+    st = lib.pf_stage_create(C.byref(c), layers, kv, 1 << 40, kv, 1 << 40, None, C.byref(out))
+    assert st in (-2, -4) and not out.value
+    assert lib.pf_last_error(None)
+
+
+def _fake_stage(lib, cfg):
+    """A stage over fake (never dereferenced) device pointers: legal as long as nothing is launched."""
+    c = B.make_config(cfg)
+    layers = (B.PfLayerWeights * cfg["n_layers"])()
+    for lw in layers:
+        for f in B._W_FIELDS:
+            setattr(lw, f, 0x100000)
+    h = C.c_void_p()
+    st = lib.pf_stage_create(C.byref(c), layers, C.c_void_p(0x200000), 1 << 40, C.c_void_p(0x300000), 1 << 40, None,
+                             C.byref(h))
+    return st, h
+
+
+def test_create_argument_errors(lib):
+    cfg = wl.CONFIGS["C1"]
+    c = B.make_config(cfg)
+    layers = (B.PfLayerWeights * 1)()
+    h = C.c_void_p()
+    assert lib.pf_stage_create(None, layers, C.c_void_p(256), 1, C.c_void_p(256), 1, None, C.byref(h)) == -1
+    assert lib.pf_stage_create(C.byref(c), layers, C.c_void_p(0x200000), 16, C.c_void_p(0x300000), 1 << 40, None,
+                               C.byref(h)) == -7                       # kv buffer too small
+    assert lib.pf_stage_create(C.byref(c), layers, C.c_void_p(0x200008), 1 << 40, C.c_void_p(0x300000), 1 << 40, None,
+                               C.byref(h)) == -7                       # misaligned
+    assert lib.pf_stage_create(C.byref(c), layers, C.c_void_p(0x200000), 1 << 40, C.c_void_p(0x300000), 1 << 40, None,
+                               C.byref(h)) == -1                       # null weight pointers
+    assert b"null" in lib.pf_last_error(None)
+
+
+def test_call_order_and_ranges_without_launching(lib):
+    st, h = _fake_stage(lib, wl.CONFIGS["C1"])
+    assert st == 0 and h.value
+    cond = B.PfCond(cond=0x400000, text=None, text_out=None)
+    x = C.c_void_p(0x500000)
+    assert lib.pf_stage_patch_forward(h, x, C.byref(cond), 0, x) == -5            # before pf_kv_init
+    assert b"pf_kv_init" in lib.pf_last_error(h)
+    assert lib.pf_stage_patch_forward(h, None, C.byref(cond), 0, x) == -1
+    assert lib.pf_stage_patch_forward(None, x, C.byref(cond), 0, x) == -1
+    v = B.PfKvView()
+    assert lib.pf_kv_view(h, 0, C.byref(v)) == 0
+    assert v.rows == 256 and v.rows_padded == 256 and v.elem_bytes == 4 and v.v_row_stride == 1
+    assert lib.pf_kv_view(h, 1, C.byref(v)) == -6
+    assert lib.pf_xattn_kv_view(h, 0, C.byref(v)) == -2
+    lib.pf_stage_destroy(h)
+    lib.pf_stage_destroy(None)                                                     # NULL-safe
+    # kind 1 needs the text features at pf_kv_init; checked before any launch
+    st, h = _fake_stage(lib, wl.CONFIGS["C2s"])
+    assert st == 0
+    empty = B.PfCond(cond=None, text=None, text_out=None)
+    assert lib.pf_kv_init(h, None, C.byref(empty), None) == -1
+    lib.pf_stage_destroy(h)
+
+
+def test_status_strings(lib):
+    assert lib.pf_status_str(0) == b"PF_OK" and lib.pf_status_str(-5) == b"PF_ERR_STATE"
+
+
+def test_op_argument_checks_without_launching(lib):
+    p = C.c_void_p(0x100000)
+    assert lib.pf_op_gemm(1, 0, p, 20, p, 20, None, p, 64, 4, 64, 20, 0, 64, 1, None, None, 0, None, 0, None) == -3
+    assert lib.pf_op_gemm(7, 0, p, 24, p, 24, None, p, 64, 4, 64, 24, 0, 64, 1, None, None, 0, None, 0, None) == -4
+    assert lib.pf_op_attention(1, 0, p, 64, p, p, 0, 128, 1, 64, p, 64, 4, 1, None, 0, None) == -3      # no key rows
+    assert lib.pf_op_attention(1, 0, p, 64, p, p, 100, 128, 1, 64, p, 64, 4, 2, None, 0, None) == -7    # no workspace
+    assert lib.pf_op_kv_scatter(1, p, 192, p, p, 128, 1, 64, 100, 64, 0, -1, 1, 1e4, None) == -3        # rows overflow
+    assert lib.pf_op_ln_modulate(0, p, 12, p, p, 1e-6, p, 12, 4, 12, 1, None) == -3

@@ -1,0 +1,230 @@
+"""Kernel-level parity (GPU): every operator of the path, called through the C boundary, against the matching
+function of the CPU oracle on the same seeded inputs.  Shapes span several tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import pf_oracle as po
+
+pytestmark = pytest.mark.gpu
+
+BF, F32 = torch.bfloat16, torch.float32
+TOL = {F32: 1e-4, BF: 2e-2}     # max|err| / rms(ref): the bars of the stage, reused per operator
+
+
+def _pkg():
+    import paper_2405_14430_amd as pkg
+    return pkg
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.Philox(key=seed))
+
+
+def _draw(rng, shape, dtype, std=1.0):
+    a = (rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
+    return wl.round_to_bf16(a) if dtype == BF else a
+
+
+def _dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(dtype)
+
+
+def _relerr(got, ref):
+    got = got.detach().double().cpu().numpy()
+    return float(np.max(np.abs(got - ref)) / (np.sqrt(np.mean(ref ** 2)) + 1e-30))
+
+
+def _log(*a):
+    print(*a, flush=True)
+
+
+def _close(got, ref, dtype, slack=1e-3):
+    """fp32: max|err| <= 2e-5 rms.  bf16 output: each element within one bf16 rounding (2^-8 relative) of the fp64
+    value plus `slack` * rms for the fp32-accumulated bf16 operands."""
+    g = got.detach().double().cpu().numpy()
+    rms = np.sqrt(np.mean(ref ** 2)) + 1e-30
+    if dtype == F32 and got.dtype == F32:
+        return float(np.max(np.abs(g - ref))) <= 2e-5 * rms
+    bound = (2.0 ** -8) * np.abs(ref) * (1.0 if got.dtype == BF else 0.0) + slack * rms
+    return bool(np.all(np.abs(g - ref) <= bound))
+
+
+@pytest.mark.parametrize("dtype", [F32, BF])
+@pytest.mark.parametrize("rows,d", [(67, 384), (130, 1152), (5, 3072), (33, 200), (9, 8192)])
+def test_ln_modulate(dtype, rows, d):
+    _log("ln_modulate", dtype, rows, d)
+    rng = _rng(rows * 10007 + d)
+    x = _draw(rng, (rows, d), F32) * 2 + 0.5
+    sh, sc = _draw(rng, (d,), F32), _draw(rng, (d,), F32)
+    got = _pkg().pf_op_ln_modulate(_dev(x, F32), _dev(sh, F32), _dev(sc, F32), 1e-6, dtype)
+    torch.cuda.synchronize()
+    assert _close(got, po.ln_modulate(x, sh, sc, 1e-6), dtype, 1e-5)
+    plain = _pkg().pf_op_ln_modulate(_dev(x, F32), None, None, 1e-6, dtype, normalize=False)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, _dev(x, F32).to(dtype))
+
+
+@pytest.mark.parametrize("dtype", [F32, BF])
+def test_modulation(dtype):
+    rng = _rng(5)
+    d, out = 1152, 6 * 1152 + 8
+    w, b, c = _draw(rng, (out, d), dtype, 0.02), _draw(rng, (out,), dtype, 0.02), _draw(rng, (d,), F32)
+    got = _pkg().pf_op_modulation(_dev(w, dtype), _dev(b, dtype), _dev(c, F32))
+    torch.cuda.synchronize()
+    assert _relerr(got, po.linear(po.silu(c), w, b)) < 1e-5
+    table, c6 = _draw(rng, (6, d), dtype, 0.02), _draw(rng, (6 * d,), F32)
+    got = _pkg().pf_op_modulation(_dev(table, dtype), None, _dev(c6, F32), table_mode=True)
+    torch.cuda.synchronize()
+    assert _relerr(got, table.reshape(-1).astype(np.float64) + c6) < 1e-6
+
+
+GEMM_SHAPES = [(67, 200, 136), (512, 3456, 1152), (130, 1152, 4608), (1, 72, 8), (300, 264, 72)]
+
+
+@pytest.mark.parametrize("dtype,path", [(F32, 1), (BF, 1), (BF, 0)])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_store_epilogue_with_gelu_columns(dtype, path, M, N, K):
+    _log("gemm/store", dtype, path, M, N, K)
+    rng = _rng(M * 31 + N * 7 + K)
+    A, W, b = _draw(rng, (M, K), dtype), _draw(rng, (N, K), dtype, 1 / math.sqrt(K)), _draw(rng, (N,), dtype)
+    gf = (N // 3) // 8 * 8
+    got = _pkg().pf_op_gemm(_dev(A, dtype), _dev(W, dtype), _dev(b, dtype), epilogue=0, gelu_from=gf, path=path)
+    torch.cuda.synchronize()
+    ref = po.linear(A, W, b)
+    ref[:, gf:] = po.gelu(ref[:, gf:], True)
+    assert _close(got, ref, dtype)
+
+
+@pytest.mark.parametrize("dtype,path", [(F32, 1), (BF, 1), (BF, 0)])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_gated_residual_epilogue(dtype, path, M, N, K):
+    _log("gemm/residual", dtype, path, M, N, K)
+    rng = _rng(M * 13 + N * 5 + K + 1)
+    A, W, b = _draw(rng, (M, K), dtype), _draw(rng, (N, K), dtype, 1 / math.sqrt(K)), _draw(rng, (N,), dtype)
+    gate, R = _draw(rng, (N,), F32), _draw(rng, (M, N), F32)
+    x, xb = _pkg().pf_op_gemm(_dev(A, dtype), _dev(W, dtype), _dev(b, dtype), epilogue=1, gate=_dev(gate, F32),
+                              R=_dev(R, F32), want_copy=True, path=path)
+    torch.cuda.synchronize()
+    ref = R.astype(np.float64) + gate.astype(np.float64) * po.linear(A, W, b)
+    assert x.dtype == F32 and _close(x, ref, dtype)
+    assert torch.equal(xb, x.to(dtype))                      # the rounded copy is the rounding of what was stored
+    # erf GELU flavour and gate = None (plain residual)
+    x2, _ = _pkg().pf_op_gemm(_dev(A, dtype), _dev(W, dtype), _dev(b, dtype), epilogue=1, R=_dev(R, F32), path=path)
+    torch.cuda.synchronize()
+    assert _close(x2, R.astype(np.float64) + po.linear(A, W, b), dtype)
+
+
+def test_gemm_erf_gelu():
+    rng = _rng(77)
+    A, W, b = _draw(rng, (40, 64), F32), _draw(rng, (48, 64), F32, 0.2), _draw(rng, (48,), F32)
+    got = _pkg().pf_op_gemm(_dev(A, F32), _dev(W, F32), _dev(b, F32), epilogue=0, gelu_from=0, gelu_tanh=0, path=1)
+    torch.cuda.synchronize()
+    assert _relerr(got, po.gelu(po.linear(A, W, b), False)) < 2e-5
+
+
+def _kv_buffers(k, v, H, dh, dtype, sentinel=None):
+    """Natural [rows, H*dh] arrays -> device K [H][Lp][dh] and V^T [H][dh][Lp] (padding rows zero)."""
+    rows = k.shape[0]
+    Lp = (rows + 127) // 128 * 128
+    K = torch.zeros(H, Lp, dh, dtype=dtype, device="cuda")
+    Vt = torch.zeros(H, dh, Lp, dtype=dtype, device="cuda")
+    K[:, :rows] = _dev(k, dtype).view(rows, H, dh).transpose(0, 1)
+    Vt[:, :, :rows] = _dev(v, dtype).view(rows, H, dh).permute(1, 2, 0)
+    return K, Vt, Lp
+
+
+@pytest.mark.parametrize("dtype", [F32, BF])
+@pytest.mark.parametrize("H,dh,rows,row0,Lp", [(4, 72, 150, 37, 384), (3, 64, 64, 0, 128), (2, 128, 70, 186, 256)])
+def test_kv_scatter_positions_bit_exact(dtype, H, dh, rows, row0, Lp):
+    """Fresh rows land at exactly rows [row0, row0+rows) of K and V^T, bit for bit; every other element of the
+    buffers keeps its bits (PipeFusion Sec. 3.3: the rest of the buffer stays one step stale)."""
+    _log("kv_scatter", dtype, H, dh, rows, row0, Lp)
+    d = H * dh
+    rng = _rng(H * 1000 + rows)
+    qkv = _dev(_draw(rng, (rows, 3 * d), dtype), dtype)
+    idt = torch.int16 if dtype == BF else torch.int32
+    K = torch.randint(-30000, 30000, (H, Lp, dh), dtype=idt, device="cuda").view(dtype)
+    Vt = torch.randint(-30000, 30000, (H, dh, Lp), dtype=idt, device="cuda").view(dtype)
+    K0, V0, q0 = K.clone(), Vt.clone(), qkv.clone()
+    _pkg().pf_op_kv_scatter(qkv, K, Vt, Lp, H, dh, row0)
+    torch.cuda.synchronize()
+    assert torch.equal(qkv.view(idt), q0.view(idt))          # without RoPE the projections are not touched
+    expK, expV = K0.clone(), V0.clone()
+    expK[:, row0:row0 + rows] = qkv[:, d:2 * d].reshape(rows, H, dh).transpose(0, 1)
+    expV[:, :, row0:row0 + rows] = qkv[:, 2 * d:].reshape(rows, H, dh).permute(1, 2, 0)
+    assert torch.equal(K.view(idt), expK.view(idt))
+    assert torch.equal(Vt.view(idt), expV.view(idt))
+
+
+@pytest.mark.parametrize("dtype", [F32, BF])
+def test_kv_scatter_rope(dtype):
+    H, dh, rows, row0, Lp, gw, tok0 = 2, 128, 75, 40, 256, 17, 91
+    d = H * dh
+    rng = _rng(99)
+    qkv_np = _draw(rng, (rows, 3 * d), dtype)
+    qkv = _dev(qkv_np, dtype)
+    K = torch.zeros(H, Lp, dh, dtype=dtype, device="cuda")
+    Vt = torch.zeros(H, dh, Lp, dtype=dtype, device="cuda")
+    _pkg().pf_op_kv_scatter(qkv, K, Vt, Lp, H, dh, row0, rope=True, tok0=tok0, grid_w=gw, theta=1e4)
+    torch.cuda.synchronize()
+    toks = np.arange(tok0, tok0 + rows)
+    ang = po.rope_angles(toks // gw, toks % gw, dh, 1e4)
+    assert _close(qkv[:, :d], po.rope_apply(qkv_np[:, :d], ang, H), dtype, 1e-4)
+    assert _close(qkv[:, d:2 * d], po.rope_apply(qkv_np[:, d:2 * d], ang, H), dtype, 1e-4)
+    assert torch.equal(qkv[:, 2 * d:], _dev(qkv_np[:, 2 * d:], dtype))
+    # the buffer holds exactly the rotated keys left in qkv, and v untouched
+    assert torch.equal(K[:, row0:row0 + rows], qkv[:, d:2 * d].reshape(rows, H, dh).transpose(0, 1))
+    assert torch.equal(Vt[:, :, row0:row0 + rows], qkv[:, 2 * d:].reshape(rows, H, dh).permute(1, 2, 0))
+    # text rows (tok0 < 0) are not rotated
+    qkv2 = _dev(qkv_np, dtype)
+    _pkg().pf_op_kv_scatter(qkv2, K, Vt, Lp, H, dh, 0, rope=True, tok0=-1, grid_w=gw)
+    torch.cuda.synchronize()
+    assert torch.equal(qkv2, _dev(qkv_np, dtype))
+
+
+ATTN_CASES = [  # H, dh, nq, Lkv, splits, gain
+    (2, 64, 70, 333, 1, 1.0), (3, 72, 200, 1000, 3, 1.0), (2, 128, 130, 515, 2, 1.0), (2, 40, 33, 120, 1, 1.0),
+    (2, 72, 129, 4096, 4, 8.0), (1, 128, 64, 700, 5, 8.0), (4, 64, 256, 64, 1, 1.0), (2, 96, 31, 257, 1, 1.0),
+]
+
+
+@pytest.mark.parametrize("dtype,path", [(F32, 1), (BF, 1), (BF, 0)])
+@pytest.mark.parametrize("H,dh,nq,Lkv,splits,gain", ATTN_CASES)
+def test_attention(dtype, path, H, dh, nq, Lkv, splits, gain):
+    """Patch queries over a full K/V buffer; gain > 1 peaks the softmax so the running-maximum rescale matters."""
+    _log("attention", dtype, path, H, dh, nq, Lkv, splits, gain)
+    d = H * dh
+    rng = _rng(H * 100003 + dh * 1009 + nq * 13 + Lkv)
+    q, k, v = _draw(rng, (nq, d), dtype, gain), _draw(rng, (Lkv, d), dtype), _draw(rng, (Lkv, d), dtype)
+    K, Vt, Lp = _kv_buffers(k, v, H, dh, dtype)
+    got = _pkg().pf_op_attention(_dev(q, dtype), K, Vt, Lkv, Lp, H, dh, splits=splits, path=path)
+    torch.cuda.synchronize()
+    assert _relerr(got, po.attention(q, k, v, H)) < TOL[dtype]
+
+
+def test_attention_ignores_finite_padding_rows():
+    """Rows beyond kv_rows never contribute, whatever finite values they hold."""
+    H, dh, nq, Lkv = 2, 72, 50, 300
+    rng = _rng(123)
+    q, k, v = _draw(rng, (nq, H * dh), BF), _draw(rng, (Lkv, H * dh), BF), _draw(rng, (Lkv, H * dh), BF)
+    K, Vt, Lp = _kv_buffers(k, v, H, dh, BF)
+    a = _pkg().pf_op_attention(_dev(q, BF), K, Vt, Lkv, Lp, H, dh)
+    K[:, Lkv:] = 50.0
+    Vt[:, :, Lkv:] = -1000.0
+    b = _pkg().pf_op_attention(_dev(q, BF), K, Vt, Lkv, Lp, H, dh)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_op_argument_errors_do_not_launch():
+    pkg = _pkg()
+    x = torch.zeros(4, 12, device="cuda")
+    with pytest.raises(pkg.PfError):
+        pkg.pf_op_ln_modulate(x, x[0], x[0], 1e-6, F32)                  # d not a multiple of 8
+    A = torch.zeros(8, 20, device="cuda")
+    with pytest.raises(pkg.PfError):
+        pkg.pf_op_gemm(A, A, None)                                       # K not a multiple of 8
