@@ -190,6 +190,12 @@ pf_status pf_kv_view(const pf_stage *stage, int layer, pf_kv_view_t *out);
 /* kind 1: the cached text keys/values of a layer's cross-attention (rows = T). */
 pf_status pf_xattn_kv_view(const pf_stage *stage, int layer, pf_kv_view_t *out);
 
+/* Host-only query: how an attention launch of `nq` query rows over the self (cross = 0) or cross-attention
+ * (cross = 1, kind 1) keys would be split over the key range, the bytes of partial results that split writes
+ * and the bytes of workspace reserved for them (ws_needed <= ws_reserved always holds). */
+pf_status pf_stage_attention_plan(const pf_stage *stage, int nq, int cross, int *splits, size_t *ws_needed,
+                                  size_t *ws_reserved);
+
 /* Change the stream later work is enqueued on (e.g. a capturing stream). */
 pf_status pf_stage_set_stream(pf_stage *stage, void *hip_stream);
 

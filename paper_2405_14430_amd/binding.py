@@ -50,7 +50,8 @@ class PfKvView(C.Structure):
 
 
 EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "pf_kv_init",
-           "pf_stage_patch_forward", "pf_kv_view", "pf_xattn_kv_view", "pf_stage_set_stream", "pf_stage_profile",
+           "pf_stage_patch_forward", "pf_kv_view", "pf_xattn_kv_view", "pf_stage_attention_plan", "pf_stage_set_stream",
+           "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention"]
 
@@ -81,6 +82,8 @@ def load_library():
     lib.pf_kv_view.argtypes = [vp, i32, C.POINTER(PfKvView)]
     lib.pf_xattn_kv_view.restype = i32
     lib.pf_xattn_kv_view.argtypes = [vp, i32, C.POINTER(PfKvView)]
+    lib.pf_stage_attention_plan.restype = i32
+    lib.pf_stage_attention_plan.argtypes = [vp, i32, i32, C.POINTER(C.c_int), C.POINTER(sz), C.POINTER(sz)]
     lib.pf_stage_set_stream.restype = i32
     lib.pf_stage_set_stream.argtypes = [vp, vp]
     lib.pf_stage_profile.restype = i32

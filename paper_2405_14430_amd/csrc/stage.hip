@@ -60,7 +60,7 @@ Derived derive(const pf_config *c) {
   d.Lkv = c->seq_img + d.Tj;
   d.Lp = (int)align_up(d.Lkv, 128);
   d.Tp = (int)align_up(d.T > 0 ? d.T : 1, 128);
-  d.Rmax = d.Lkv;
+  d.Rmax = d.Lkv > d.T ? d.Lkv : d.T;   // rows of the largest pass (warm-up) and of the kind-1 text projection
   d.mod_chunks = c->kind == PF_BLOCK_SINGLE_STREAM ? 3 : 6;
   d.n_streams = c->kind == PF_BLOCK_MMDIT_JOINT ? 2 : 1;
   d.esz = dt_size(c->dtype);
@@ -118,7 +118,8 @@ WsLayout ws_layout(const pf_config *c, const Derived &d) {
   }
   const int path = use_path(c);
   size_t ab = 0;
-  int shapes[2] = {d.n + d.Tj, d.Rmax};
+  // every query-row count a call can have: image-only patch, patch with the joint text rows, warm-up pass
+  int shapes[3] = {d.n, d.n + d.Tj, d.Lkv};
   for (int nq : shapes) {
     size_t b = attention_ws_bytes(nq, c->n_heads, c->head_dim, choose_splits(path, nq, c->n_heads, d.Lkv));
     if (b > ab) ab = b;
@@ -204,13 +205,22 @@ hipError_t gemm(pf_stage *s, int cls, const void *A, int64_t lda, const void *W,
   return run(s, cls, [&] { return launch_gemm(g, s->stream); });
 }
 
+// Split count of an attention launch of this stage: the occupancy heuristic, lowered if needed so that the partial
+// results never exceed the workspace region reserved for them.
+int plan_splits(const pf_stage *s, int nq, int kv_rows) {
+  const int path = use_path(&s->cfg);
+  int splits = choose_splits(path, nq, s->cfg.n_heads, kv_rows);
+  while (splits > 1 && attention_ws_bytes(nq, s->cfg.n_heads, s->cfg.head_dim, splits) > s->w.attn_bytes) --splits;
+  return splits;
+}
+
 hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const void *kb, const void *vb, int kv_rows,
                      int rows_padded, void *out, int64_t ldo, int nq) {
   AttnArgs a{};
   a.dt = s->cfg.dtype; a.path = use_path(&s->cfg);
   a.q = q; a.ldq = ldq; a.kbuf = kb; a.vtbuf = vb; a.kv_rows = kv_rows; a.rows_padded = rows_padded;
   a.n_heads = s->cfg.n_heads; a.head_dim = s->cfg.head_dim; a.out = out; a.ldo = ldo; a.nq = nq;
-  a.splits = choose_splits(a.path, nq, a.n_heads, kv_rows);
+  a.splits = plan_splits(s, nq, kv_rows);
   a.ws = (float *)(s->ws + s->w.attn);
   hipError_t e = run(s, cls, [&] { return a.path == PATH_SIMT ? launch_attn_simt(a, s->stream) : launch_attn_mfma(a, s->stream); });
   if (e != hipSuccess) return e;
@@ -428,6 +438,17 @@ static pf_status fill_view(const pf_stage *s, int layer, bool cross, pf_kv_view_
 
 pf_status pf_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, false, out); }
 pf_status pf_xattn_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, true, out); }
+
+pf_status pf_stage_attention_plan(const pf_stage *s, int nq, int cross, int *splits, size_t *ws_needed,
+                                  size_t *ws_reserved) {
+  if (!s || !splits || !ws_needed || !ws_reserved) return PF_ERR_NULL;
+  if (nq < 1 || nq > s->d.Lkv) return PF_ERR_RANGE;
+  if (cross && s->cfg.kind != PF_BLOCK_ADALN_SINGLE_XATTN) return PF_ERR_CONFIG;
+  *splits = plan_splits(s, nq, cross ? s->d.T : s->d.Lkv);
+  *ws_needed = attention_ws_bytes(nq, s->cfg.n_heads, s->cfg.head_dim, *splits);
+  *ws_reserved = s->w.attn_bytes;
+  return PF_OK;
+}
 
 pf_status pf_stage_set_stream(pf_stage *s, void *hip_stream) {
   if (!s) return PF_ERR_NULL;

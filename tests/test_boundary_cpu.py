@@ -72,9 +72,13 @@ def _fake_stage(lib, cfg):
     """A stage over fake (never dereferenced) device pointers: legal as long as nothing is launched."""
     c = B.make_config(cfg)
     layers = (B.PfLayerWeights * cfg["n_layers"])()
-    for lw in layers:
+    txt = (B.PfLayerWeights * cfg["n_layers"])()
+    for lw, tw in zip(layers, txt):
         for f in B._W_FIELDS:
             setattr(lw, f, 0x100000)
+            setattr(tw, f, 0x100000)
+        if cfg["kind"] == 2:
+            lw.txt = C.pointer(tw)
     h = C.c_void_p()
     st = lib.pf_stage_create(C.byref(c), layers, C.c_void_p(0x200000), 1 << 40, C.c_void_p(0x300000), 1 << 40, None,
                              C.byref(h))
@@ -132,3 +136,21 @@ def test_op_argument_checks_without_launching(lib):
     assert lib.pf_op_attention(1, 0, p, 64, p, p, 100, 128, 1, 64, p, 64, 4, 2, None, 0, None) == -7    # no workspace
     assert lib.pf_op_kv_scatter(1, p, 192, p, p, 128, 1, 64, 100, 64, 0, -1, 1, 1e4, None) == -3        # rows overflow
     assert lib.pf_op_ln_modulate(0, p, 12, p, p, 1e-6, p, 12, 4, 12, 1, None) == -3
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5", "C3s", "C4s"])
+def test_attention_partials_always_fit_the_reserved_workspace(lib, name):
+    """Whatever row count a call has (image-only patch, patch plus joint text rows, warm-up pass, anything
+    between), the split-KV partial results stay inside the workspace region reserved for them."""
+    cfg = wl.CONFIGS[name]
+    st, h = _fake_stage(lib, cfg)
+    assert st == 0
+    n, Lkv, Tj = wl.patch_rows(cfg), wl.kv_rows(cfg), wl.joint_text_rows(cfg)
+    splits, need, have = C.c_int(), C.c_size_t(), C.c_size_t()
+    probe = sorted({1, 63, 64, 65, 127, 128, 129, n - 1, n, n + 1, n + Tj, Lkv // 2, Lkv - 1, Lkv} & set(range(1, Lkv + 1)))
+    for nq in probe + list(range(1, Lkv + 1, max(1, Lkv // 257))):
+        for cross in ([0, 1] if cfg["kind"] == 1 else [0]):
+            assert lib.pf_stage_attention_plan(h, nq, cross, C.byref(splits), C.byref(need), C.byref(have)) == 0
+            assert need.value <= have.value and splits.value >= 1, (nq, cross)
+    assert lib.pf_stage_attention_plan(h, Lkv + 1, 0, C.byref(splits), C.byref(need), C.byref(have)) == -6
+    lib.pf_stage_destroy(h)
