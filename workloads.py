@@ -21,12 +21,16 @@ KIND_MMDIT_JOINT = 2         # SD3: two weight streams, one joint attention
 KIND_SINGLE_STREAM = 3       # Flux single-stream: parallel attn+MLP, 2-D RoPE
 
 _BASE = dict(text_len=0, cross_dim=0, ln_eps=1e-6, rope_theta=1e4, gelu_tanh=1,
-             w_std=0.02, qk_gain=1.0)
+             w_std=0.02, qk_gain=1.0, cond_std=None)
 
 
 def _cfg(**kw):
     c = dict(_BASE)
     c.update(kw)
+    if c["cond_std"] is None:
+        # fp32 workloads: conditioning embedding N(0,1).  bf16 workloads: N(0, 0.5^2), which with N(0,0.02)
+        # modulation weights gives shift/scale/gate vectors of std 0.1-0.2, the range of trained adaLN blocks.
+        c["cond_std"] = 1.0 if c["dtype"] == "f32" else 0.5
     assert c["hidden"] == c["n_heads"] * c["head_dim"]
     assert c["seq_img"] == c["grid_h"] * c["grid_w"]
     assert c["seq_img"] % c["n_patches"] == 0
@@ -164,7 +168,15 @@ def make_activations(cfg, noise=0.05):
     out = {}
     out["x"] = _store(cfg, _normal(rng, (L, d)))
     out["x_prev"] = _store(cfg, out["x"] + np.float32(noise) * _normal(rng, (L, d)))
-    out["cond"] = _store(cfg, _normal(rng, (6 * d if kind == KIND_ADALN_SINGLE_XATTN else d,)))
+    if kind == KIND_ADALN_SINGLE_XATTN:
+        # adaLN-single: the stage receives the model-global 6d projection of the conditioning embedding, not
+        # the embedding itself.  It is drawn at the scale that projection has under the workload's own weight
+        # distribution, std(W) * sqrt(d) * rms(SiLU(c)) with rms(SiLU(c)) ~ 0.55 std(c): the same scale the
+        # other kinds' per-layer modulation Linear produces from their embedding.
+        w_std = (1.0 / np.sqrt(d)) if cfg["w_std"] == "fan_in" else float(cfg["w_std"])
+        out["cond"] = _store(cfg, _normal(rng, (6 * d,), w_std * np.sqrt(d) * 0.55 * cfg["cond_std"]))
+    else:
+        out["cond"] = _store(cfg, _normal(rng, (d,), cfg["cond_std"]))
     if kind == KIND_ADALN_SINGLE_XATTN:
         out["text"] = _store(cfg, _normal(rng, (T, cfg["cross_dim"])))
     elif kind in (KIND_MMDIT_JOINT, KIND_SINGLE_STREAM):
