@@ -272,6 +272,10 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
                           void *out, int64_t ldo, int nq, int splits, void *ws, size_t ws_bytes,
                           void *stream);
 
+/* Tuning hook for the bf16 GEMM: 0 = the library's own tile heuristic (default); other values pin one tile
+ * configuration for every following launch of the process (used by the tile sweeps behind the heuristic). */
+void pf_tune_gemm_tile(int id);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,412 @@
+// bf16 MFMA GEMMs with direct global->LDS loads (gfx950): C = epilogue(A W^T + bias), A [M,K], W [N,K], both
+// contiguous along K, K a multiple of 64.
+//
+// Tiles are brought in with global_load_lds_dwordx4: one instruction moves 64 x 16 B = 1 KB = eight 128-byte tile
+// rows (64 bf16 of K each), lane l filling row l/8, 16-byte slot l%8.  The LDS side of such a load is lane-linear (no
+// padding possible), so bank conflicts are avoided with an XOR swizzle: chunk c (8 bf16) of tile row r is kept in slot
+// c ^ ((r >> 1) & 7); the loading lane picks its global chunk accordingly and the MFMA fragment reads undo it.  Rows
+// beyond M (or N) are clamped to the last valid row: they only feed accumulators that the epilogue never stores.
+//
+// Two kernels share that machinery:
+//  * gemm_tile_kernel<BM,BN,NSTAGE>: 2x2 wavefronts share one BM x BN tile; NSTAGE LDS stages, one s_barrier per K
+//    tile.  For GEMMs with enough tiles to fill the chip.
+//  * gemm_wavek_kernel<BM,BN>: for skinny GEMMs (n = 512 patch rows: a few hundred tiles at most).  The four
+//    wavefronts of a workgroup split K between them: each streams its own K tiles through a private two-stage LDS
+//    ring with no workgroup barrier in the loop, which quadruples the loads in flight per CU and divides the serial
+//    chain of K iterations by four; the four partial tiles are then summed through LDS.
+// Both finish through LDS: the fp32 tile is laid out row-major and every thread applies the epilogue to runs of 8
+// consecutive columns (16-byte bf16 stores, 32-byte fp32 stores).
+#include "common.h"
+#include "epilogue.h"
+#include "ops.h"
+
+namespace pf {
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int ROW_BYTES = BK * 2;  // 128
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void lds_load16(const bf16_t *g, unsigned char *lds_wave_uniform) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                   (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
+}
+
+// Epilogue over a finished fp32 tile held row-major in LDS (row stride TLD floats).
+template <int BM, int BN, int TLD>
+__device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0, int M, int N, const Epilogue<bf16_t> &epi,
+                                              bool vec_ok) {
+  constexpr int GROUPS = BM * BN / 8;
+  for (int g = threadIdx.x; g < GROUPS; g += 256) {
+    const int r = g / (BN / 8), c0 = (g % (BN / 8)) * 8;
+    const int row = m0 + r, col = n0 + c0;
+    if (row >= M || col >= N) continue;
+    const float *src = tile + r * TLD + c0;
+    float4 lo = *reinterpret_cast<const float4 *>(src), hi4 = *reinterpret_cast<const float4 *>(src + 4);
+    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi4.x, hi4.y, hi4.z, hi4.w};
+    if (!vec_ok || col + 8 > N) {
+      for (int e = 0; e < 8 && col + e < N; ++e) epi.apply(row, col + e, v[e]);
+      continue;
+    }
+    if (epi.bias) {
+      bf16x8 b = *reinterpret_cast<const bf16x8 *>(epi.bias + col);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += (float)b[e];
+    }
+    if (epi.mode == 0) {
+      if (col + 8 > epi.gelu_from) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (col + e >= epi.gelu_from) v[e] = gelu_f(v[e], epi.gelu_tanh);
+      }
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+      *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(epi.C) + (size_t)row * epi.ldc + col) = o;
+    } else {
+      const float *rp = epi.R + (size_t)row * epi.ldr + col;
+      float4 r0 = *reinterpret_cast<const float4 *>(rp), r1 = *reinterpret_cast<const float4 *>(rp + 4);
+      float x[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+      if (epi.gate) {
+        float4 g0 = *reinterpret_cast<const float4 *>(epi.gate + col), g1 = *reinterpret_cast<const float4 *>(epi.gate + col + 4);
+        float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] += gg[e] * v[e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] += v[e];
+      }
+      float *xp = reinterpret_cast<float *>(epi.C) + (size_t)row * epi.ldc + col;
+      *reinterpret_cast<float4 *>(xp) = make_float4(x[0], x[1], x[2], x[3]);
+      *reinterpret_cast<float4 *>(xp + 4) = make_float4(x[4], x[5], x[6], x[7]);
+      if (epi.C2) {
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)x[e];
+        *reinterpret_cast<bf16x8 *>(epi.C2 + (size_t)row * epi.ldc2 + col) = o;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// 2x2 wavefronts on one shared tile
+// ------------------------------------------------------------------------------------------------------------------
+template <int BM, int BN, int NSTAGE>
+__global__ __launch_bounds__(256) void gemm_tile_kernel(const bf16_t *__restrict__ A, int64_t lda,
+                                                        const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
+                                                        Epilogue<bf16_t> epi, int vec_ok) {
+  constexpr int WM = BM / 2, WN = BN / 2;
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int LA = BM / 32, LW = BN / 32;  // load instructions per wave per stage
+  constexpr int LPS = LA + LW;
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  constexpr int TLD = BN + 4;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+  const bf16_t *pa[LA];
+  const bf16_t *pw[LW];
+#pragma unroll
+  for (int i = 0; i < LA; ++i) {
+    int r = (i * 4 + wave) * 8 + (lane >> 3);
+    int c = (lane & 7) ^ ((r >> 1) & 7);
+    pa[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < LW; ++i) {
+    int r = (i * 4 + wave) * 8 + (lane >> 3);
+    int c = (lane & 7) ^ ((r >> 1) & 7);
+    pw[i] = W + (size_t)min(n0 + r, N - 1) * ldw + c * 8;
+  }
+  auto issue = [&](int stage, int kt) {
+    unsigned char *sa = smem + stage * STAGE_BYTES;
+    unsigned char *sw = sa + BM * ROW_BYTES;
+    const int koff = kt * BK;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) lds_load16(pa[i] + koff, sa + (i * 4 + wave) * 1024);
+#pragma unroll
+    for (int i = 0; i < LW; ++i) lds_load16(pw[i] + koff, sw + (i * 4 + wave) * 1024);
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / BK;
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nk) issue(s, s);
+
+  const int l32 = lane & 31, hi = lane >> 5;
+  int arow[MI], akey[MI], wrow[NI], wkey[NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    int r = wm * WM + i * 32 + l32;
+    arow[i] = r * ROW_BYTES;
+    akey[i] = (r >> 1) & 7;
+  }
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    int r = wn * WN + j * 32 + l32;
+    wrow[j] = BM * ROW_BYTES + r * ROW_BYTES;
+    wkey[j] = (r >> 1) & 7;
+  }
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // tiles still in flight behind tile kt: min(NSTAGE-2, nk-1-kt)
+    const int behind = min(NSTAGE - 2, nk - 1 - kt);
+    if (behind >= 2) wait_vmcnt<2 * LPS>();
+    else if (behind == 1) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+    // plain s_barrier: __syncthreads() would also drain every global load in flight (vmcnt(0)), i.e. the prefetches
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt + NSTAGE - 1 < nk) issue((kt + NSTAGE - 1) % NSTAGE, kt + NSTAGE - 1);
+    const unsigned char *st = smem + (kt % NSTAGE) * STAGE_BYTES;
+    // Fragments are read from LDS PRE k-steps ahead of the MFMAs that use them: with one accumulator per wave
+    // (64x64 tile) a k-step is a single MFMA, far shorter than an LDS read, so the whole tile is preloaded.
+    constexpr int KS = BK / 16;
+    constexpr int PRE = (MI * NI <= 2) ? KS : 2;
+    bf16x8 af[PRE][MI], wf[PRE][NI];
+    auto lread = [&](int buf, int ks) {
+      const int c = ks * 2 + hi;
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + arow[i] + ((c ^ akey[i]) << 4));
+#pragma unroll
+      for (int j = 0; j < NI; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8 *>(st + wrow[j] + ((c ^ wkey[j]) << 4));
+    };
+#pragma unroll
+    for (int ks = 0; ks < PRE - 1; ++ks) lread(ks, ks);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + PRE - 1 < KS) lread((ks + PRE - 1) % PRE, ks + PRE - 1);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks % PRE][i], wf[ks % PRE][j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // accumulators -> row-major fp32 tile in LDS (lane -> column l32, register r -> row 8*(r/4) + 4*hi + r%4)
+  __syncthreads();
+  float *tile = reinterpret_cast<float *>(smem);
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        tile[(wm * WM + i * 32 + 8 * (r >> 2) + 4 * hi + (r & 3)) * TLD + wn * WN + j * 32 + l32] = acc[i][j][r];
+  __syncthreads();
+  tile_epilogue<BM, BN, TLD>(tile, m0, n0, M, N, epi, vec_ok != 0);
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// four wavefronts split K; each owns a private two-stage ring for its own BM x BN x 64 tiles
+// ------------------------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_wavek_kernel(const bf16_t *__restrict__ A, int64_t lda,
+                                                         const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
+                                                         Epilogue<bf16_t> epi, int vec_ok) {
+  constexpr int MI = BM / 32, NI = BN / 32;
+  constexpr int LA = BM / 8, LW = BN / 8;   // load instructions per wave per stage (a wave loads whole tiles)
+  constexpr int LPS = LA + LW;
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  constexpr int WAVE_BYTES = 2 * STAGE_BYTES;
+  constexpr int TLD = BN + 4;
+  static_assert(LPS <= 31, "two stages of loads must fit the vmcnt counter");
+  static_assert(WAVE_BYTES >= BM * TLD * 4, "a wave's partial tile must fit in its own ring");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  unsigned char *ring = smem + wave * WAVE_BYTES;
+
+  // K tiles of this wave: wave, wave + 4, ...
+  const int nk = K / BK;
+  const int my_nk = (nk - wave + 3) / 4;
+
+  const int lr = lane >> 3, lc = lane & 7;
+  auto issue = [&](int stage, int t) {   // t-th tile of this wave; instruction i covers tile rows 8i .. 8i+7
+    unsigned char *sa = ring + stage * STAGE_BYTES;
+    unsigned char *sw = sa + BM * ROW_BYTES;
+    const int koff = (wave + 4 * t) * BK;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      int r = i * 8 + lr;
+      int c = lc ^ ((r >> 1) & 7);
+      lds_load16(A + (size_t)min(m0 + r, M - 1) * lda + koff + c * 8, sa + i * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+      int r = i * 8 + lr;
+      int c = lc ^ ((r >> 1) & 7);
+      lds_load16(W + (size_t)min(n0 + r, N - 1) * ldw + koff + c * 8, sw + i * 1024);
+    }
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  if (my_nk > 0) issue(0, 0);
+  if (my_nk > 1) issue(1, 1);
+
+  const int l32 = lane & 31, hi = lane >> 5;
+  for (int t = 0; t < my_nk; ++t) {
+    if (t + 1 < my_nk) wait_vmcnt<LPS>(); else wait_vmcnt<0>();
+    asm volatile("" ::: "memory");
+    const unsigned char *st = ring + (t & 1) * STAGE_BYTES;
+    bf16x8 af[2][MI], wf[2][NI];
+    auto lread = [&](int buf, int ks) {
+      const int c = ks * 2 + hi;
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        int r = i * 32 + l32;
+        af[buf][i] = *reinterpret_cast<const bf16x8 *>(st + r * ROW_BYTES + ((c ^ ((r >> 1) & 7)) << 4));
+      }
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        int r = j * 32 + l32;
+        wf[buf][j] = *reinterpret_cast<const bf16x8 *>(st + (BM + r) * ROW_BYTES + ((c ^ ((r >> 1) & 7)) << 4));
+      }
+    };
+    lread(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      if (ks + 1 < BK / 16) lread((ks + 1) & 1, ks + 1);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], wf[ks & 1][j], acc[i][j], 0, 0, 0);
+    }
+    // this wave's LDS reads of the stage are complete (the MFMAs above consumed them): refill it
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (t + 2 < my_nk) issue(t & 1, t + 2);
+  }
+
+  // partial tiles -> LDS (each wave into its own ring), then sum of the four and epilogue
+  float *part = reinterpret_cast<float *>(ring);
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        part[(i * 32 + 8 * (r >> 2) + 4 * hi + (r & 3)) * TLD + j * 32 + l32] = acc[i][j][r];
+  __syncthreads();
+  float *p0 = reinterpret_cast<float *>(smem);
+  constexpr int WSTRIDE = WAVE_BYTES / 4;
+  for (int e = tid; e < BM * BN / 4; e += 256) {
+    int r = e / (BN / 4), c = (e % (BN / 4)) * 4;
+    float4 s0 = *reinterpret_cast<const float4 *>(p0 + r * TLD + c);
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      float4 s1 = *reinterpret_cast<const float4 *>(p0 + w * WSTRIDE + r * TLD + c);
+      s0.x += s1.x; s0.y += s1.y; s0.z += s1.z; s0.w += s1.w;
+    }
+    *reinterpret_cast<float4 *>(p0 + r * TLD + c) = s0;
+  }
+  __syncthreads();
+  tile_epilogue<BM, BN, TLD>(p0, m0, n0, M, N, epi, vec_ok != 0);
+}
+
+bool vec_epilogue_ok(const GemmArgs &a) {
+  auto al = [](const void *p, uintptr_t n) { return ((uintptr_t)p % n) == 0; };
+  bool ok = (!a.bias || al(a.bias, 16));
+  if (a.epilogue == 0) return ok && al(a.C, 16) && a.ldc % 8 == 0;
+  ok = ok && al(a.C, 16) && a.ldc % 4 == 0 && al(a.R, 16) && a.ldr % 4 == 0 && (!a.gate || al(a.gate, 16));
+  if (a.C2) ok = ok && al(a.C2, 16) && a.ldc2 % 8 == 0;
+  return ok;
+}
+
+template <int BM, int BN, int NSTAGE>
+hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
+  // the stage ring, or the fp32 tile (row stride BN + 4) that replaces it for the epilogue, whichever is larger
+  constexpr int ring = NSTAGE * (BM + BN) * ROW_BYTES, tile = BM * (BN + 4) * 4;
+  constexpr int smem = ring > tile ? ring : tile;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, NSTAGE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  dim3 g((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
+  gemm_tile_kernel<BM, BN, NSTAGE><<<g, 256, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
+                                                       a.K, make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0);
+  return hipGetLastError();
+}
+
+template <int BM, int BN>
+hipError_t launch_wavek(const GemmArgs &a, hipStream_t s) {
+  constexpr int smem = 4 * 2 * (BM + BN) * ROW_BYTES;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wavek_kernel<BM, BN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  dim3 g((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
+  gemm_wavek_kernel<BM, BN><<<g, 256, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N, a.K,
+                                                make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= BK && a.M >= 1 && a.N >= 1; }
+
+int g_gemm_tile_override = 0;   // tuning hook: 0 = heuristic, 1.. = a fixed tile configuration
+
+hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
+  switch (g_gemm_tile_override) {
+    case 1: return launch_tile<256, 128, 3>(a, s);
+    case 2: return launch_tile<128, 128, 3>(a, s);
+    case 3: return launch_tile<128, 128, 2>(a, s);
+    case 4: return launch_tile<128, 64, 4>(a, s);
+    case 5: return launch_tile<64, 64, 4>(a, s);
+    case 6: return launch_tile<256, 128, 2>(a, s);
+    case 7: return launch_tile<128, 64, 2>(a, s);
+    case 8: return launch_tile<64, 64, 2>(a, s);
+    case 9: return launch_gemm_mfma(a, s);
+    case 10: return launch_wavek<64, 64>(a, s);
+    case 11: return launch_wavek<64, 32>(a, s);
+    case 12: return launch_wavek<32, 64>(a, s);
+    case 13: return launch_wavek<32, 32>(a, s);
+    default: break;
+  }
+  auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+  // Measured on MI355X: 128x128 (two workgroups per CU) is the fastest tile once it yields >= 1.5 workgroups per CU;
+  // below that the 64x64 tile wins, and when K is long and tiles are few the K-splitting kernel does.
+  if (tiles(128, 128) >= 384) return launch_tile<128, 128, 2>(a, s);
+  if (tiles(128, 64) >= 512) return launch_tile<128, 64, 2>(a, s);
+  if (tiles(64, 64) < 512 && a.K >= 2048) return launch_wavek<64, 64>(a, s);
+  return launch_tile<64, 64, 2>(a, s);
+}
+
+}  // namespace pf

@@ -61,6 +61,8 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);   // bytes mu
 // kernel-path specific pieces (defined in gemm_*.hip / attn_*.hip)
 hipError_t launch_gemm_simt(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);
+bool gemm_mfma_dl_supported(const GemmArgs &a);            // direct-to-LDS multi-stage variant (K % 64 == 0)
+hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s);
 hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);

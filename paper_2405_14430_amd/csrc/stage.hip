@@ -576,8 +576,12 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 
 }  // extern "C"
 
+namespace pf { extern int g_gemm_tile_override; }
+extern "C" void pf_tune_gemm_tile(int id) { pf::g_gemm_tile_override = id; }
+
 namespace pf {
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s) {
-  return a.path == PATH_SIMT || a.dt != DT_BF16 ? launch_gemm_simt(a, s) : launch_gemm_mfma(a, s);
+  if (a.path == PATH_SIMT || a.dt != DT_BF16) return launch_gemm_simt(a, s);
+  return gemm_mfma_dl_supported(a) ? launch_gemm_mfma_dl(a, s) : launch_gemm_mfma(a, s);
 }
 }  // namespace pf

@@ -82,7 +82,8 @@ def test_modulation(dtype):
     assert _relerr(got, table.reshape(-1).astype(np.float64) + c6) < 1e-6
 
 
-GEMM_SHAPES = [(67, 200, 136), (512, 3456, 1152), (130, 1152, 4608), (1, 72, 8), (300, 264, 72)]
+GEMM_SHAPES = [(67, 200, 136), (512, 3456, 1152), (130, 1152, 4608), (1, 72, 8), (300, 264, 72), (257, 130, 192),
+               (2100, 1000, 640), (4100, 2050, 128), (33, 70, 64)]
 
 
 @pytest.mark.parametrize("dtype,path", [(F32, 1), (BF, 1), (BF, 0)])
