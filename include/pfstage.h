@@ -273,7 +273,8 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
                           void *stream);
 
 /* Tuning hook for the bf16 GEMM: 0 = the library's own tile heuristic (default); other values pin one tile
- * configuration for every following launch of the process (used by the tile sweeps behind the heuristic). */
+ * configuration for every following launch of the process (used by the tile sweeps behind the heuristic).
+ * Values 100 + v select the attention kernel generation instead (100 = default). */
 void pf_tune_gemm_tile(int id);
 
 #ifdef __cplusplus

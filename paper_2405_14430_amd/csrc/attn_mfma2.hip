@@ -1,0 +1,322 @@
+// Flash-style patch attention for gfx950, head sizes 64 / 72 / 128 (bf16 operands, fp32 accumulation and softmax).
+//
+// The patch's queries attend over ALL rows of the layer's K/V buffer, fresh and stale alike (PipeFusion Sec. 3.3).
+// Per workgroup: 128 queries (4 wavefronts x 32) of one head and one split of the key range.  The arithmetic layout is
+// the transposed one (a lane owns one query column):
+//   S^T[kv][q] = K[kv][:] . Q[q][:]        A = K tile (LDS), B = Q fragments (registers)
+//   O^T[c][q] += V^T[c][kv] . P^T[kv][q]   A = V^T tile (LDS), B = P^T straight from the S^T accumulator registers
+// so the online-softmax statistics are in-lane reductions plus one exchange with lane^32 and the O^T rescale is per lane.
+//
+// K tiles ([64 kv][dh], contiguous in the head-major buffer) and V^T tiles ([dh][64 kv]) come in with
+// global_load_lds_dwordx4 into a two-stage LDS ring (one s_barrier per tile, prefetch of tile t+1 in flight during tile
+// t).  The LDS side of those loads is lane-linear, so bank conflicts are handled by XOR-swizzling the 16-byte chunks of a
+// row (the loading lane fetches the chunk that belongs at its LDS slot); dh = 72 rows are 144 bytes, which is conflict
+// free without a swizzle.  Workgroup ids are remapped so that all workgroups of one head run on the same XCD and share
+// its L2 for that head's K/V.
+#include "common.h"
+#include "ops.h"
+
+namespace pf {
+
+namespace {
+
+constexpr int TQ = 128;
+constexpr int TK = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void lds_load16(const void *g, unsigned char *lds_wave_uniform) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                   (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
+}
+
+template <int DH>
+struct Cfg {
+  static constexpr int KS16 = DH / 16;
+  static constexpr bool TAIL8 = (DH % 16) == 8;
+  static constexpr int KROW = DH * 2;                    // bytes per K tile row
+  static constexpr int KCHUNKS = DH / 8;                 // 16-byte chunks per K row
+  static constexpr int K_BYTES = TK * KROW;
+  static constexpr int K_INSTR = K_BYTES / 1024;         // 1 KB per load instruction
+  static constexpr int CB = (DH + 31) / 32;
+  static constexpr int V_ROWS = CB * 32;
+  static constexpr int V_BYTES = V_ROWS * 128;
+  static constexpr int V_INSTR = DH / 8;                 // 8 rows of 128 B per instruction
+  static constexpr int STAGE = K_BYTES + V_BYTES;
+  static constexpr int LK = (K_INSTR + 3) / 4, LV = (V_INSTR + 3) / 4;   // instructions per wave
+  static constexpr int LPS = LK + LV;
+  // swizzle key of K row r (applied to the chunk index)
+  static __device__ __forceinline__ int kkey(int r) {
+    return DH == 64 ? ((r >> 1) & 7) : (DH == 128 ? (r & 15) : 0);
+  }
+};
+
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__restrict__ q, int64_t ldq,
+                                                            const bf16_t *__restrict__ kbuf,
+                                                            const bf16_t *__restrict__ vtbuf, int kv_rows, int Lp, int H,
+                                                            bf16_t *__restrict__ out, int64_t ldo, int nq, int splits,
+                                                            int qtiles, float *__restrict__ ws) {
+  using C = Cfg<DH>;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hi = lane >> 5;
+
+  // ---- workgroup id -> (head, query tile, split), heads grouped per XCD (ids are dealt round-robin to the 8 XCDs)
+  const int total = gridDim.x;
+  int L = blockIdx.x;
+  const int per_xcd = total >> 3;
+  if (L < per_xcd * 8) L = (L & 7) * per_xcd + (L >> 3);
+  const int per_head = qtiles * splits;
+  const int h = L / per_head;
+  const int rem = L - h * per_head;
+  const int qt = rem / splits, sp = rem - qt * splits;
+  const int q0 = qt * TQ + wave * 32;
+
+  // ---- zero the V^T padding rows (never written by the tile loads) of both stages
+  if constexpr (C::V_ROWS > DH) {
+    constexpr int PADB = (C::V_ROWS - DH) * 128;
+    for (int e = tid; e < 2 * PADB / 16; e += 256) {
+      int st = e / (PADB / 16), o = e % (PADB / 16);
+      *reinterpret_cast<uint4 *>(smem + st * C::STAGE + C::K_BYTES + DH * 128 + o * 16) = make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  const int tiles = (kv_rows + TK - 1) / TK;
+  const int tps = (tiles + splits - 1) / splits;
+  const int t_begin = sp * tps, t_end = min(tiles, (sp + 1) * tps);
+  const unsigned char *kh = reinterpret_cast<const unsigned char *>(kbuf + (size_t)h * Lp * DH);
+  const bf16_t *vh = vtbuf + (size_t)h * DH * Lp;
+
+  // ---- per-lane source offsets of this wave's load instructions
+  int koff[C::LK];      // byte offset inside a K tile
+  unsigned char *kdst[C::LK];
+#pragma unroll
+  for (int i = 0; i < C::LK; ++i) {
+    int ins = min(i * 4 + wave, C::K_INSTR - 1);          // surplus slots repeat the last instruction (same data)
+    int off = ins * 1024 + lane * 16;
+    int r = off / C::KROW, p = (off % C::KROW) >> 4;
+    koff[i] = r * C::KROW + ((p ^ C::kkey(r)) << 4);
+    kdst[i] = smem + ins * 1024;
+  }
+  int64_t voff[C::LV];  // element offset inside the head's V^T (without the tile's column offset)
+  unsigned char *vdst[C::LV];
+#pragma unroll
+  for (int i = 0; i < C::LV; ++i) {
+    int ins = min(i * 4 + wave, C::V_INSTR - 1);
+    int r = ins * 8 + (lane >> 3), p = lane & 7;
+    voff[i] = (int64_t)r * Lp + ((p ^ ((r >> 1) & 7)) << 3);
+    vdst[i] = smem + C::K_BYTES + ins * 1024;
+  }
+  auto issue = [&](int stage, int t) {
+    const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
+    const bf16_t *vsrc = vh + (size_t)t * TK;
+#pragma unroll
+    for (int i = 0; i < C::LK; ++i) lds_load16(ksrc + koff[i], kdst[i] + stage * C::STAGE);
+#pragma unroll
+    for (int i = 0; i < C::LV; ++i) lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
+  };
+  if (t_begin < t_end) issue(0, t_begin);
+
+  // ---- Q fragments (B operand): lane holds query q0 + l32, channels ks*16 + 8*hi .. +7
+  bf16x8 qf[C::KS16];
+  bf16x4 qtail = {0, 0, 0, 0};
+  {
+    const int qi = q0 + l32;
+    const bf16_t *qp = q + (size_t)qi * ldq + (size_t)h * DH;
+#pragma unroll
+    for (int ks = 0; ks < C::KS16; ++ks) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (qi < nq) v = *reinterpret_cast<const uint4 *>(qp + ks * 16 + hi * 8);
+      qf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+    if constexpr (C::TAIL8) {
+      uint2 v = make_uint2(0, 0);
+      if (qi < nq) v = *reinterpret_cast<const uint2 *>(qp + C::KS16 * 16 + hi * 4);
+      qtail = __builtin_bit_cast(bf16x4, v);
+    }
+  }
+
+  f32x16 oacc[C::CB];
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;   // running maximum of the raw scores; per-lane partial sum
+  const float sl2 = kLog2e / sqrtf((float)DH);
+
+  // fragment addressing, loop invariant
+  int krow_off[2], kkeyv[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    int r = b * 32 + l32;
+    krow_off[b] = r * C::KROW;
+    kkeyv[b] = C::kkey(r);
+  }
+  int vrow_off[C::CB], vkey[C::CB];
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb) {
+    int r = cb * 32 + l32;
+    vrow_off[cb] = C::K_BYTES + r * 128 + 8 * hi;
+    vkey[cb] = (r >> 1) & 7;
+  }
+
+  __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int stage = (t - t_begin) & 1;
+    wait_vmcnt<0>();                      // tile t (the only one in flight for this wave) has landed
+    __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the other stage
+    asm volatile("" ::: "memory");
+    if (t + 1 < t_end) issue(stage ^ 1, t + 1);
+    const unsigned char *st = smem + stage * C::STAGE;
+
+    // ---- S^T = K . Q^T for the two 32-row blocks of the tile
+    f32x16 sacc[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < C::KS16; ++ks) {
+        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + krow_off[b] + (((ks * 2 + hi) ^ kkeyv[b]) << 4));
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[b], 0, 0, 0);
+      }
+      if constexpr (C::TAIL8) {
+        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(st + krow_off[b] + C::KS16 * 32 + hi * 8);
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, kf4),
+                                                           __builtin_bit_cast(short4v, qtail), sacc[b], 0, 0, 0);
+      }
+    }
+    // ---- online softmax on raw scores (the positive scale commutes with max)
+    if ((t + 1) * TK > kv_rows) {
+      const int jbase = t * TK + 4 * hi;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (jbase + b * 32 + 8 * (r >> 2) + (r & 3) >= kv_rows) sacc[b][r] = -INFINITY;
+    }
+    float tmax = sacc[0][0];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[b][r]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
+    const float mneg = -m_new * sl2;
+    m_run = m_new;
+    float psum = 0.f;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], sl2, mneg));
+        psum += p;
+        pf[b][r >> 3][r & 7] = (bf16_t)p;
+      }
+    l_run = l_run * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // skip the rescale when no lane's maximum moved
+#pragma unroll
+      for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+    }
+    // ---- O^T += V^T . P^T
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb) {
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const int ch = b * 4 + s2 * 2;
+          uint2 lo = *reinterpret_cast<const uint2 *>(st + vrow_off[cb] + ((ch ^ vkey[cb]) << 4));
+          uint2 hi2 = *reinterpret_cast<const uint2 *>(st + vrow_off[cb] + (((ch + 1) ^ vkey[cb]) << 4));
+          uint4 both = make_uint4(lo.x, lo.y, hi2.x, hi2.y);
+          oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[b][s2], oacc[cb], 0, 0, 0);
+        }
+    }
+  }
+  wait_vmcnt<0>();
+
+  // ---- finish
+  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  const int qi = q0 + l32;
+  if (qi >= nq) return;
+  const int d = H * DH;
+  if (splits == 1) {
+    const float inv = 1.f / l_tot;
+    bf16_t *op = out + (size_t)qi * ldo + (size_t)h * DH;
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int c = cb * 32 + 8 * g + 4 * hi;
+        if (c < DH) {
+          bf16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = (bf16_t)(oacc[cb][4 * g + e] * inv);
+          *reinterpret_cast<bf16x4 *>(op + c) = o4;
+        }
+      }
+  } else {
+    float *op = ws + ((size_t)sp * nq + qi) * d + (size_t)h * DH;
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int c = cb * 32 + 8 * g + 4 * hi;
+        if (c < DH)
+          *reinterpret_cast<float4 *>(op + c) =
+              make_float4(oacc[cb][4 * g], oacc[cb][4 * g + 1], oacc[cb][4 * g + 2], oacc[cb][4 * g + 3]);
+      }
+    if (hi == 0) {
+      float *ml = ws + (size_t)splits * nq * d + (((size_t)sp * nq + qi) * H + h) * 2;
+      ml[0] = m_run * sl2 * kLn2;   // natural-log domain maximum of the scaled scores, for the combine kernel
+      ml[1] = l_tot;
+    }
+  }
+}
+
+template <int DH>
+hipError_t launch2(const AttnArgs &a, hipStream_t s) {
+  using C = Cfg<DH>;
+  constexpr int smem = 2 * C::STAGE;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int qtiles = (a.nq + TQ - 1) / TQ;
+  dim3 g(qtiles * a.n_heads * a.splits);
+  attn_mfma2_kernel<DH><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
+                                             a.kv_rows, a.rows_padded, a.n_heads, (bf16_t *)a.out, a.ldo, a.nq, a.splits,
+                                             qtiles, a.ws);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma2_supported(const AttnArgs &a) {
+  return (a.head_dim == 64 || a.head_dim == 72 || a.head_dim == 128) && a.rows_padded % TK == 0;
+}
+
+hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s) {
+  if (a.nq <= 0) return hipSuccess;
+  if (a.head_dim == 64) return launch2<64>(a, s);
+  if (a.head_dim == 72) return launch2<72>(a, s);
+  return launch2<128>(a, s);
+}
+
+}  // namespace pf

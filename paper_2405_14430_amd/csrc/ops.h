@@ -65,6 +65,9 @@ bool gemm_mfma_dl_supported(const GemmArgs &a);            // direct-to-LDS mult
 hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s);
 hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
+bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS variant for head sizes 64 / 72 / 128
+hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s);
+hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s);   // picks between the two
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);
 
 }  // namespace pf

@@ -222,7 +222,7 @@ hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const voi
   a.n_heads = s->cfg.n_heads; a.head_dim = s->cfg.head_dim; a.out = out; a.ldo = ldo; a.nq = nq;
   a.splits = plan_splits(s, nq, kv_rows);
   a.ws = (float *)(s->ws + s->w.attn);
-  hipError_t e = run(s, cls, [&] { return a.path == PATH_SIMT ? launch_attn_simt(a, s->stream) : launch_attn_mfma(a, s->stream); });
+  hipError_t e = run(s, cls, [&] { return a.path == PATH_SIMT ? launch_attn_simt(a, s->stream) : launch_attn_bf16(a, s->stream); });
   if (e != hipSuccess) return e;
   if (a.splits > 1) e = run(s, PF_KC_ATTN_COMBINE, [&] { return launch_attn_combine(a, s->stream); });
   return e;
@@ -569,7 +569,7 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
   a.q = q; a.ldq = ldq; a.kbuf = kbuf; a.vtbuf = vtbuf; a.kv_rows = kv_rows; a.rows_padded = rows_padded; a.n_heads = n_heads;
   a.head_dim = head_dim; a.out = out; a.ldo = ldo; a.nq = nq; a.splits = splits; a.ws = (float *)ws;
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = a.path == PATH_SIMT ? launch_attn_simt(a, st) : launch_attn_mfma(a, st);
+  hipError_t e = a.path == PATH_SIMT ? launch_attn_simt(a, st) : launch_attn_bf16(a, st);
   if (e == hipSuccess && splits > 1) e = launch_attn_combine(a, st);
   return e == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
@@ -577,9 +577,16 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 }  // extern "C"
 
 namespace pf { extern int g_gemm_tile_override; }
-extern "C" void pf_tune_gemm_tile(int id) { pf::g_gemm_tile_override = id; }
+namespace pf { extern int g_attn_variant; }
+extern "C" void pf_tune_gemm_tile(int id) {
+  if (id >= 100) pf::g_attn_variant = id - 100; else pf::g_gemm_tile_override = id;
+}
 
 namespace pf {
+int g_attn_variant = 0;   // tuning hook: 0 = newest kernel that supports the shape, 1 = first-generation kernel
+hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s) {
+  return (g_attn_variant == 0 && attn_mfma2_supported(a)) ? launch_attn_mfma2(a, s) : launch_attn_mfma(a, s);
+}
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s) {
   if (a.path == PATH_SIMT || a.dt != DT_BF16) return launch_gemm_simt(a, s);
   return gemm_mfma_dl_supported(a) ? launch_gemm_mfma_dl(a, s) : launch_gemm_mfma(a, s);
