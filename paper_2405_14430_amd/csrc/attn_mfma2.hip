@@ -11,8 +11,12 @@
 // global_load_lds_dwordx4 into a two-stage LDS ring (one s_barrier per tile, prefetch of tile t+1 in flight during tile
 // t).  The LDS side of those loads is lane-linear, so bank conflicts are handled by XOR-swizzling the 16-byte chunks of a
 // row (the loading lane fetches the chunk that belongs at its LDS slot); dh = 72 rows are 144 bytes, which is conflict
-// free without a swizzle.  Workgroup ids are remapped so that all workgroups of one head run on the same XCD and share
+// free without a swizzle.  Before the PV product the two half-waves exchange half of their packed P registers
+// (v_permlane32_swap) so that each lane's eight P values cover eight CONSECUTIVE kv rows; the matching V^T operand is
+// then a single 16-byte LDS read.  Workgroup ids are remapped so that all workgroups of one head run on the same XCD and share
 // its L2 for that head's K/V.
+#include <type_traits>
+
 #include "common.h"
 #include "ops.h"
 
@@ -152,26 +156,27 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   float m_run = -INFINITY, l_run = 0.f;   // running maximum of the raw scores; per-lane partial sum
   const float sl2 = kLog2e / sqrtf((float)DH);
 
-  // fragment addressing, loop invariant
-  int krow_off[2], kkeyv[2];
+  // fragment addressing, loop invariant: address = row base + ((chunk ^ key) << 4); the chunk's low bit is the
+  // half-wave index, so it is folded into the per-lane key and the rest of the chunk index is a compile-time XOR mask
+  int krow_off[2], kx[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     int r = b * 32 + l32;
     krow_off[b] = r * C::KROW;
-    kkeyv[b] = C::kkey(r);
+    kx[b] = (hi ^ C::kkey(r)) << 4;
   }
-  int vrow_off[C::CB], vkey[C::CB];
+  int vrow_off[C::CB], vx[C::CB];
 #pragma unroll
   for (int cb = 0; cb < C::CB; ++cb) {
     int r = cb * 32 + l32;
-    vrow_off[cb] = C::K_BYTES + r * 128 + 8 * hi;
-    vkey[cb] = (r >> 1) & 7;
+    vrow_off[cb] = C::K_BYTES + r * 128;
+    vx[cb] = (hi ^ ((r >> 1) & 7)) << 4;
   }
 
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
 
-  for (int t = t_begin; t < t_end; ++t) {
-    const int stage = (t - t_begin) & 1;
+  auto tile_step = [&](int t, auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
     wait_vmcnt<0>();                      // tile t (the only one in flight for this wave) has landed
     __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the other stage
     asm volatile("" ::: "memory");
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
       for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < C::KS16; ++ks) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + krow_off[b] + (((ks * 2 + hi) ^ kkeyv[b]) << 4));
+        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + krow_off[b] + (kx[b] ^ (ks << 5)));
         sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[b], 0, 0, 0);
       }
       if constexpr (C::TAIL8) {
@@ -215,14 +220,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
     const float mneg = -m_new * sl2;
     m_run = m_new;
     float psum = 0.f;
-    bf16x8 pf[2][2];
+    unsigned pk[2][8];   // packed bf16 pairs (r, r+1) of the softmax weights
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], sl2, mneg));
-        psum += p;
-        pf[b][r >> 3][r & 7] = (bf16_t)p;
+      for (int r = 0; r < 16; r += 2) {
+        float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], sl2, mneg));
+        float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r + 1], sl2, mneg));
+        psum += p0 + p1;
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
+        pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
       }
     l_run = l_run * alpha + psum;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // skip the rescale when no lane's maximum moved
@@ -231,20 +239,32 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
     }
-    // ---- O^T += V^T . P^T
+    // ---- O^T += V^T . P^T.  For each K=16 step the half-waves trade registers so that lane-half `hi` holds the
+    // weights of kv rows 16*step + 8*hi .. +7 (in order); V^T supplies the same rows with one 16-byte read.
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        auto x0 = __builtin_amdgcn_permlane32_swap(pk[b][4 * s2], pk[b][4 * s2 + 2], false, false);
+        auto x1 = __builtin_amdgcn_permlane32_swap(pk[b][4 * s2 + 1], pk[b][4 * s2 + 3], false, false);
+        uint4 u = make_uint4(x0[0], x1[0], x0[1], x1[1]);
+        pf[b][s2] = __builtin_bit_cast(bf16x8, u);
+      }
 #pragma unroll
     for (int cb = 0; cb < C::CB; ++cb) {
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const int ch = b * 4 + s2 * 2;
-          uint2 lo = *reinterpret_cast<const uint2 *>(st + vrow_off[cb] + ((ch ^ vkey[cb]) << 4));
-          uint2 hi2 = *reinterpret_cast<const uint2 *>(st + vrow_off[cb] + (((ch + 1) ^ vkey[cb]) << 4));
-          uint4 both = make_uint4(lo.x, lo.y, hi2.x, hi2.y);
-          oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[b][s2], oacc[cb], 0, 0, 0);
+          bf16x8 vf = *reinterpret_cast<const bf16x8 *>(st + vrow_off[cb] + (vx[cb] ^ ((2 * b + s2) << 5)));
+          oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[b][s2], oacc[cb], 0, 0, 0);
         }
     }
+  };
+  for (int t = t_begin; t < t_end; t += 2) {
+    tile_step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < t_end) tile_step(t + 1, std::integral_constant<int, 1>{});
   }
   wait_vmcnt<0>();
 
