@@ -38,11 +38,11 @@ __device__ __forceinline__ void lds_load16(const bf16_t *g, unsigned char *lds_w
 }
 
 // Epilogue over a finished fp32 tile held row-major in LDS (row stride TLD floats).
-template <int BM, int BN, int TLD>
+template <int BM, int BN, int TLD, int NT = 256>
 __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0, int M, int N, const Epilogue<bf16_t> &epi,
                                               bool vec_ok) {
   constexpr int GROUPS = BM * BN / 8;
-  for (int g = threadIdx.x; g < GROUPS; g += 256) {
+  for (int g = threadIdx.x; g < GROUPS; g += NT) {
     const int r = g / (BN / 8), c0 = (g % (BN / 8)) * 8;
     const int row = m0 + r, col = n0 + c0;
     if (row >= M || col >= N) continue;
@@ -95,15 +95,17 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
 }
 
 // ------------------------------------------------------------------------------------------------------------------
-// 2x2 wavefronts on one shared tile
+// WGM x WGN wavefronts on one shared tile
 // ------------------------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NSTAGE>
-__global__ __launch_bounds__(256) void gemm_tile_kernel(const bf16_t *__restrict__ A, int64_t lda,
+template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t *__restrict__ A, int64_t lda,
                                                         const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
                                                         Epilogue<bf16_t> epi, int vec_ok) {
-  constexpr int WM = BM / 2, WN = BN / 2;
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int MI = WM / 32, NI = WN / 32;
-  constexpr int LA = BM / 32, LW = BN / 32;  // load instructions per wave per stage
+  constexpr int LA = BM / 8 / NW, LW = BN / 8 / NW;  // load instructions per wave per stage
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split evenly over the waves' load instructions");
   constexpr int LPS = LA + LW;
   constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
   constexpr int TLD = BN + 4;
@@ -112,20 +114,20 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const bf16_t *__restrict
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
   const bf16_t *pa[LA];
   const bf16_t *pw[LW];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
-    int r = (i * 4 + wave) * 8 + (lane >> 3);
+    int r = (i * NW + wave) * 8 + (lane >> 3);
     int c = (lane & 7) ^ ((r >> 1) & 7);
     pa[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
-    int r = (i * 4 + wave) * 8 + (lane >> 3);
+    int r = (i * NW + wave) * 8 + (lane >> 3);
     int c = (lane & 7) ^ ((r >> 1) & 7);
     pw[i] = W + (size_t)min(n0 + r, N - 1) * ldw + c * 8;
   }
@@ -134,9 +136,9 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const bf16_t *__restrict
     unsigned char *sw = sa + BM * ROW_BYTES;
     const int koff = kt * BK;
 #pragma unroll
-    for (int i = 0; i < LA; ++i) lds_load16(pa[i] + koff, sa + (i * 4 + wave) * 1024);
+    for (int i = 0; i < LA; ++i) lds_load16(pa[i] + koff, sa + (i * NW + wave) * 1024);
 #pragma unroll
-    for (int i = 0; i < LW; ++i) lds_load16(pw[i] + koff, sw + (i * 4 + wave) * 1024);
+    for (int i = 0; i < LW; ++i) lds_load16(pw[i] + koff, sw + (i * NW + wave) * 1024);
   };
 
   f32x16 acc[MI][NI];
@@ -203,18 +205,29 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const bf16_t *__restrict
     }
   }
 
-  // accumulators -> row-major fp32 tile in LDS (lane -> column l32, register r -> row 8*(r/4) + 4*hi + r%4)
-  __syncthreads();
+  // accumulators -> row-major fp32 tile in LDS (lane -> column l32, register r -> row 8*(r/4) + 4*hi + r%4), in
+  // passes of RB rows when the whole tile does not fit in the stage memory
+  constexpr int RING = NSTAGE * STAGE_BYTES;
+  constexpr int RB = (BM * TLD * 4 <= RING) ? BM : ((BM / 2) * TLD * 4 <= RING ? BM / 2 : BM / 4);
+  static_assert(RB * TLD * 4 <= RING || RB == BM, "epilogue pass does not fit");
+  static_assert(RB % WM == 0 || WM % RB == 0, "pass rows and wave rows must nest");
   float *tile = reinterpret_cast<float *>(smem);
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+  for (int pass = 0; pass < BM / RB; ++pass) {
+    __syncthreads();
 #pragma unroll
-    for (int j = 0; j < NI; ++j)
+    for (int i = 0; i < MI; ++i) {
+      const int rbase = wm * WM + i * 32;          // first tile row of this 32-row block
+      if (rbase / RB != pass) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        tile[(wm * WM + i * 32 + 8 * (r >> 2) + 4 * hi + (r & 3)) * TLD + wn * WN + j * 32 + l32] = acc[i][j][r];
-  __syncthreads();
-  tile_epilogue<BM, BN, TLD>(tile, m0, n0, M, N, epi, vec_ok != 0);
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          tile[(rbase - pass * RB + 8 * (r >> 2) + 4 * hi + (r & 3)) * TLD + wn * WN + j * 32 + l32] = acc[i][j][r];
+    }
+    __syncthreads();
+    tile_epilogue<RB, BN, TLD, 64 * NW>(tile, m0 + pass * RB, n0, M, N, epi, vec_ok != 0);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -343,20 +356,20 @@ bool vec_epilogue_ok(const GemmArgs &a) {
   return ok;
 }
 
-template <int BM, int BN, int NSTAGE>
+template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2>
 hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
   // the stage ring, or the fp32 tile (row stride BN + 4) that replaces it for the epilogue, whichever is larger
   constexpr int ring = NSTAGE * (BM + BN) * ROW_BYTES, tile = BM * (BN + 4) * 4;
-  constexpr int smem = ring > tile ? ring : tile;
+  constexpr int smem = (tile > ring && tile <= 96 * 1024) ? tile : ring;   // larger tiles finish in row passes
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, NSTAGE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   dim3 g((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
-  gemm_tile_kernel<BM, BN, NSTAGE><<<g, 256, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
+  gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
                                                        a.K, make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0);
   return hipGetLastError();
 }
@@ -398,11 +411,18 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 11: return launch_wavek<64, 32>(a, s);
     case 12: return launch_wavek<32, 64>(a, s);
     case 13: return launch_wavek<32, 32>(a, s);
+    case 14: return launch_tile<256, 128, 3, 4, 2>(a, s);
+    case 15: return launch_tile<256, 256, 2, 4, 2>(a, s);
+    case 16: return launch_tile<128, 256, 3, 2, 4>(a, s);
+    case 17: return launch_tile<256, 128, 2, 4, 2>(a, s);
+    case 18: return launch_tile<256, 256, 2, 2, 2>(a, s);
     default: break;
   }
   auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
   // Measured on MI355X: 128x128 (two workgroups per CU) is the fastest tile once it yields >= 1.5 workgroups per CU;
   // below that the 64x64 tile wins, and when K is long and tiles are few the K-splitting kernel does.
+  if (tiles(256, 256) >= 1024) return launch_tile<256, 256, 2, 4, 2>(a, s);   // 8 waves, least L1 traffic per flop
+  if (tiles(256, 128) >= 512) return launch_tile<256, 128, 2, 4, 2>(a, s);
   if (tiles(128, 128) >= 384) return launch_tile<128, 128, 2>(a, s);
   if (tiles(128, 64) >= 512) return launch_tile<128, 64, 2>(a, s);
   if (tiles(64, 64) < 512 && a.K >= 2048) return launch_wavek<64, 64>(a, s);
