@@ -10,9 +10,29 @@ namespace pf {
 // modulation: mod = W * SiLU(c) + b   (one wave per output), or mod = table + c
 // ------------------------------------------------------------------------------------------------
 template <typename T>
+__device__ __forceinline__ void modulation_body(const T *__restrict__ w, const T *__restrict__ b,
+                                                const float *__restrict__ c, float *__restrict__ mod, int out_dim,
+                                                int in_dim, int table_mode);
+
+template <typename T>
 __global__ __launch_bounds__(256) void modulation_kernel(const T *__restrict__ w, const T *__restrict__ b,
                                                          const float *__restrict__ c, float *__restrict__ mod,
                                                          int out_dim, int in_dim, int table_mode) {
+  modulation_body<T>(w, b, c, mod, out_dim, in_dim, table_mode);
+}
+
+// blockIdx.y selects the (layer, stream) entry
+template <typename T>
+__global__ __launch_bounds__(256) void modulation_batch_kernel(ModBatch mb, const float *__restrict__ c, int out_dim,
+                                                               int in_dim, int table_mode) {
+  const int e = blockIdx.y;
+  modulation_body<T>((const T *)mb.w[e], (const T *)mb.b[e], c, mb.out[e], out_dim, in_dim, table_mode);
+}
+
+template <typename T>
+__device__ __forceinline__ void modulation_body(const T *__restrict__ w, const T *__restrict__ b,
+                                                const float *__restrict__ c, float *__restrict__ mod, int out_dim,
+                                                int in_dim, int table_mode) {
   if (table_mode) {
     int j = blockIdx.x * 256 + threadIdx.x;
     if (j < out_dim) mod[j] = to_f32(w[j]) + c[j];
@@ -38,6 +58,16 @@ __global__ __launch_bounds__(256) void modulation_kernel(const T *__restrict__ w
     acc = wave_sum(acc);
     if (lane == 0) mod[j] = acc + to_f32(b[j]);
   }
+}
+
+hipError_t launch_modulation_batch(int dt, const ModBatch &mb, const float *c, int out_dim, int in_dim, int table_mode,
+                                   hipStream_t s) {
+  if (mb.count <= 0) return hipSuccess;
+  dim3 g(table_mode ? (out_dim + 255) / 256 : (out_dim + 31) / 32, mb.count);
+  size_t sh = table_mode ? 0 : (size_t)in_dim * sizeof(float);
+  if (dt == DT_BF16) modulation_batch_kernel<bf16_t><<<g, 256, sh, s>>>(mb, c, out_dim, in_dim, table_mode);
+  else modulation_batch_kernel<float><<<g, 256, sh, s>>>(mb, c, out_dim, in_dim, table_mode);
+  return hipGetLastError();
 }
 
 hipError_t launch_modulation(int dt, const void *w, const void *b, const float *c, float *mod, int out_dim,

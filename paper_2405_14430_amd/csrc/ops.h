@@ -16,6 +16,17 @@ inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
 hipError_t launch_modulation(int dt, const void *w, const void *b, const float *c, float *mod, int out_dim,
                              int in_dim, int table_mode, hipStream_t s);
 
+// Up to kMax modulation vectors (layers x streams) in one launch; all share cond and the shapes.
+struct ModBatch {
+  static constexpr int kMax = 16;
+  const void *w[kMax];
+  const void *b[kMax];
+  float *out[kMax];
+  int count;
+};
+hipError_t launch_modulation_batch(int dt, const ModBatch &mb, const float *c, int out_dim, int in_dim, int table_mode,
+                                   hipStream_t s);
+
 hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *shift, const float *scale,
                               float eps, void *out, int64_t ldo, int rows, int d, int normalize,
                               hipStream_t s);

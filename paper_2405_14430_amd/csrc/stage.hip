@@ -244,18 +244,39 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
   float *xres = (float *)(ws + w.xres);
   char *h = ws + w.h, *qkv = ws + w.qkv, *a = ws + w.a, *u = ws + w.u;
 
-  if (Tt) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres, text, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
-  PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres + (size_t)Tt * D, x_img, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  // Residual rows.  With text rows riding along they are gathered in the workspace, text first.  Without, nothing is
+  // copied: the first layer reads x_img directly, the first residual GEMM writes into the output buffer (or the
+  // workspace when the caller wants no output) and everything after that runs in place there.
+  float *xbuf = xres;          // where updated residual rows live
+  const float *xsrc = xres;    // where the current residual rows are read from (x_img until the first update)
+  if (Tt) {
+    PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres, text, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+    PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres + (size_t)Tt * D, x_img, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  } else {
+    xsrc = x_img;
+    if (y_img) xbuf = y_img;
+  }
 
-  // a0: modulation vectors of every layer (and stream)
-  for (int l = 0; l < c.n_layers; ++l) {
-    for (int si = 0; si < d.n_streams; ++si) {
-      if (c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt) continue;   // text stream idle
-      const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
-      const int out_dim = d.mod_chunks * D;
-      const int table = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
-      PF_TRY(run(s, PF_KC_MODULATION, [&] { return launch_modulation(dt, lw.w_mod, lw.b_mod, cond, s->mod(si, l), out_dim, D, table, st); }));
+  // a0: modulation vectors of every layer (and stream), one launch per 16 of them
+  {
+    ModBatch mb{};
+    const int out_dim = d.mod_chunks * D;
+    const int table = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
+    auto flush = [&]() -> hipError_t {
+      if (mb.count == 0) return hipSuccess;
+      hipError_t e2 = run(s, PF_KC_MODULATION, [&] { return launch_modulation_batch(dt, mb, cond, out_dim, D, table, st); });
+      mb.count = 0;
+      return e2;
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+      for (int si = 0; si < d.n_streams; ++si) {
+        if (c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt) continue;   // text stream idle
+        const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
+        mb.w[mb.count] = lw.w_mod; mb.b[mb.count] = lw.b_mod; mb.out[mb.count] = s->mod(si, l);
+        if (++mb.count == ModBatch::kMax) PF_TRY(flush());
+      }
     }
+    PF_TRY(flush());
   }
 
   const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
@@ -264,7 +285,7 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
     if (c.kind == PF_BLOCK_SINGLE_STREAM) {
       const pf_layer_weights &lw = s->img[l];
       const float *m = s->mod(0, l);
-      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xres, D, m, m + D, c.ln_eps, h, D, R, D, 1, st); }));
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xsrc, D, m, m + D, c.ln_eps, h, D, R, D, 1, st); }));
       PF_TRY(gemm(s, PF_KC_GEMM_QKV, h, D, lw.w_qkv, D, lw.b_qkv, qkv, 3 * D, R, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0, nullptr, 0));
       // MLP branch runs in parallel with attention: GELU(h W_up^T + b) lands right of the attention columns
       PF_TRY(gemm(s, PF_KC_GEMM_UP, h, D, lw.w_up, D, lw.b_up, a + (size_t)D * e, D + F, R, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
@@ -273,7 +294,8 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       sa.qkv = qkv + (size_t)Tt * 3 * D * e; sa.row0 = row0_img; sa.rows = n_img; sa.tok0 = img_off;
       PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
       PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D + F, R));
-      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xres, D, R, D, D + F, 1, 0, m + 2 * D, xres, D, nullptr, 0));
+      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xbuf, D, R, D, D + F, 1, 0, m + 2 * D, xsrc, D, nullptr, 0));
+      xsrc = xbuf;
       continue;
     }
 
@@ -286,7 +308,7 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
 
     for (int si = 0; si < ns; ++si) {
       const Stream &sm = streams[si];
-      const float *xs = xres + (size_t)sm.r0 * D;
+      const float *xs = xsrc + (size_t)sm.r0 * D;
       char *hs = h + (size_t)sm.r0 * D * e;
       char *qs = qkv + (size_t)sm.r0 * 3 * D * e;
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, sm.nr, D, 1, st); }));
@@ -297,13 +319,14 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
     PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R));
     for (int si = 0; si < ns; ++si) {
       const Stream &sm = streams[si];
-      float *xs = xres + (size_t)sm.r0 * D;
+      float *xs = xbuf + (size_t)sm.r0 * D;
+      const float *xs_in = xsrc + (size_t)sm.r0 * D;   // differs from xs only before the first update
       char *hs = h + (size_t)sm.r0 * D * e;
       char *as = a + (size_t)sm.r0 * D * e;
       char *us = u + (size_t)sm.r0 * F * e;
       const bool xattn = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
       char *xb = xattn ? ws + w.xb : nullptr;
-      PF_TRY(gemm(s, PF_KC_GEMM_OUT, as, D, sm.lw->w_o, D, sm.lw->b_o, xs, D, sm.nr, D, D, 1, 0, sm.m + 2 * D, xs, D, xb, D));
+      PF_TRY(gemm(s, PF_KC_GEMM_OUT, as, D, sm.lw->w_o, D, sm.lw->b_o, xs, D, sm.nr, D, D, 1, 0, sm.m + 2 * D, xs_in, D, xb, D));
       if (xattn) {
         char *qc = ws + w.qc;
         PF_TRY(gemm(s, PF_KC_GEMM_XATTN, xb, D, sm.lw->xattn_wq, D, sm.lw->xattn_bq, qc, D, sm.nr, D, D, 0, D, nullptr, nullptr, 0, nullptr, 0));
@@ -314,9 +337,10 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       PF_TRY(gemm(s, PF_KC_GEMM_UP, hs, D, sm.lw->w_up, D, sm.lw->b_up, us, F, sm.nr, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
       PF_TRY(gemm(s, PF_KC_GEMM_DOWN, us, F, sm.lw->w_down, F, sm.lw->b_down, xs, D, sm.nr, D, F, 1, 0, sm.m + 5 * D, xs, D, nullptr, 0));
     }
+    xsrc = xbuf;   // every stream of this layer has written its rows
   }
 
-  if (y_img) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(y_img, xres + (size_t)Tt * D, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  if (y_img && xbuf != y_img) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(y_img, xres + (size_t)Tt * D, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
   if (Tt && text_out) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(text_out, xres, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
   return PF_OK;
 }

@@ -119,6 +119,30 @@ def test_gemm_gated_residual_epilogue(dtype, path, M, N, K):
     assert _close(x2, R.astype(np.float64) + po.linear(A, W, b), dtype)
 
 
+@pytest.mark.parametrize("tile_id", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18])
+def test_gemm_every_tile_configuration(tile_id):
+    """Each bf16 tile configuration the heuristic can pick (and the ones it currently does not), pinned through the
+    tuning hook, on a shape with ragged M and N, for both epilogues."""
+    pkg = _pkg()
+    lib = pkg.load_library()
+    M, N, K = 777, 650, 320
+    rng = _rng(4242 + tile_id)
+    A, W, b = _draw(rng, (M, K), BF), _draw(rng, (N, K), BF, 1 / math.sqrt(K)), _draw(rng, (N,), BF)
+    gate, R = _draw(rng, (N,), F32), _draw(rng, (M, N), F32)
+    lib.pf_tune_gemm_tile(tile_id)
+    try:
+        got = pkg.pf_op_gemm(_dev(A, BF), _dev(W, BF), _dev(b, BF), epilogue=0, gelu_from=320)
+        x, xb = pkg.pf_op_gemm(_dev(A, BF), _dev(W, BF), _dev(b, BF), epilogue=1, gate=_dev(gate, F32), R=_dev(R, F32),
+                               want_copy=True)
+        torch.cuda.synchronize()
+    finally:
+        lib.pf_tune_gemm_tile(0)
+    ref = po.linear(A, W, b)
+    refx = R.astype(np.float64) + gate.astype(np.float64) * ref
+    ref[:, 320:] = po.gelu(ref[:, 320:], True)
+    assert _close(got, ref, BF) and _close(x, refx, BF) and torch.equal(xb, x.to(BF))
+
+
 def test_gemm_erf_gelu():
     rng = _rng(77)
     A, W, b = _draw(rng, (40, 64), F32), _draw(rng, (48, 64), F32, 0.2), _draw(rng, (48,), F32)
