@@ -37,6 +37,20 @@ __device__ __forceinline__ void lds_load16(const bf16_t *g, unsigned char *lds_w
                                    (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
 }
 
+// Workgroup id -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2; giving every
+// XCD one contiguous run of tiles (ordered with the larger operand's tile index slowest) makes that operand come in
+// from memory once for the whole chip instead of once per XCD.  Returns false for the surplus ids of the padded grid.
+__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int n_major, int &tm, int &tn) {
+  const int T = tiles_m * tiles_n;
+  const int per = (T + 7) >> 3;
+  const int id = blockIdx.x;
+  const int L = (id & 7) * per + (id >> 3);
+  if ((id >> 3) >= per || L >= T) return false;
+  if (n_major) { tn = L / tiles_m; tm = L - tn * tiles_m; }
+  else { tm = L / tiles_n; tn = L - tm * tiles_n; }
+  return true;
+}
+
 // Epilogue over a finished fp32 tile held row-major in LDS (row stride TLD floats).
 template <int BM, int BN, int TLD, int NT = 256>
 __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0, int M, int N, const Epilogue<bf16_t> &epi,
@@ -100,7 +114,7 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
 template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t *__restrict__ A, int64_t lda,
                                                         const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
-                                                        Epilogue<bf16_t> epi, int vec_ok) {
+                                                        Epilogue<bf16_t> epi, int vec_ok, int n_major) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int MI = WM / 32, NI = WN / 32;
@@ -115,7 +129,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  int tm, tn;
+  if (!tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, n_major, tm, tn)) return;
+  const int m0 = tm * BM, n0 = tn * BN;
 
   const bf16_t *pa[LA];
   const bf16_t *pw[LW];
@@ -236,7 +252,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
 template <int BM, int BN>
 __global__ __launch_bounds__(256) void gemm_wavek_kernel(const bf16_t *__restrict__ A, int64_t lda,
                                                          const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
-                                                         Epilogue<bf16_t> epi, int vec_ok) {
+                                                         Epilogue<bf16_t> epi, int vec_ok, int n_major) {
   constexpr int MI = BM / 32, NI = BN / 32;
   constexpr int LA = BM / 8, LW = BN / 8;   // load instructions per wave per stage (a wave loads whole tiles)
   constexpr int LPS = LA + LW;
@@ -250,7 +266,9 @@ __global__ __launch_bounds__(256) void gemm_wavek_kernel(const bf16_t *__restric
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  int tm, tn;
+  if (!tile_of_block((M + BM - 1) / BM, (N + BN - 1) / BN, n_major, tm, tn)) return;
+  const int m0 = tm * BM, n0 = tn * BN;
   unsigned char *ring = smem + wave * WAVE_BYTES;
 
   // K tiles of this wave: wave, wave + 4, ...
@@ -368,9 +386,11 @@ hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  dim3 g((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
+  const int64_t T = (int64_t)((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
+  dim3 g((unsigned)(((T + 7) / 8) * 8));
   gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
-                                                       a.K, make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0);
+                                                       a.K, make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0,
+                                                       a.N >= a.M ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -384,9 +404,10 @@ hipError_t launch_wavek(const GemmArgs &a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  dim3 g((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
+  const int64_t T = (int64_t)((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
+  dim3 g((unsigned)(((T + 7) / 8) * 8));
   gemm_wavek_kernel<BM, BN><<<g, 256, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N, a.K,
-                                                make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0);
+                                                make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0, a.N >= a.M ? 1 : 0);
   return hipGetLastError();
 }
 
