@@ -140,8 +140,15 @@ def main():
         if b:
             kernels[c]["gbs"] = b / (kernels[c]["avg_us"] * 1e-6) / 1e9
     ach = kernels[dom]["tflops"]
+    # HBM-side bytes per launch of the dominant kernel, from committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload.lower()}.json")
+    if os.path.exists(tpath):
+        t = json.load(open(tpath)).get("kernels", {}).get(dom)
+        if t:
+            traffic = t["fetch_bytes"] + t["write_bytes"]
     roofline = {"kernel": dom, "bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "achieved": ach, "peak": peak,
-                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
                 "avg_launch_us": kernels[dom]["avg_us"],
                 "flops_per_launch": flops_per_launch(cfg, dom, n)}
 
