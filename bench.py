@@ -74,6 +74,7 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--path", type=int, default=0, help="0 auto (MFMA for bf16), 1 force SIMT kernels")
+    ap.add_argument("--tune", type=int, nargs="*", default=[], help="values for the library's tuning hook (A/B runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the multi-GPU pipeline schedule is out of scope); "
@@ -95,7 +96,9 @@ def main():
     text = None
     if A["text"] is not None:
         text = dev(A["text"]).to(dt) if cfg["kind"] == 1 else dev(A["text"])
-    st = Stage(cfg, W)
+    st = Stage(cfg, W, kernel_path=args.path)
+    for t in args.tune:
+        st.lib.pf_tune_gemm_tile(t)
     st.kv_init(dev(A["x_prev"]), cond, text)
     x = dev(A["x"])
     xs = [x[p * n:(p + 1) * n].contiguous() for p in range(M)]

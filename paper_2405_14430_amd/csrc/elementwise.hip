@@ -328,6 +328,33 @@ hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// RoPE (cos, sin) table of a call's rows: first half of a head's channel pairs <- grid row, second half <- grid column
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_table_kernel(float2 *__restrict__ tab, int rows, int n_text, int tok0,
+                                                         int grid_w, int dh, float theta) {
+  const int half = dh >> 1, quarter = dh >> 2;
+  int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (int64_t)rows * half) return;
+  const int r = (int)(id / half), j = (int)(id % half);
+  float cs = 1.f, sn = 0.f;
+  if (r >= n_text) {
+    const int tok = tok0 + (r - n_text);
+    const int ia = j < quarter ? j : j - quarter;
+    const float pos = j < quarter ? (float)(tok / grid_w) : (float)(tok % grid_w);
+    const float freq = exp2f(-log2f(theta) * (4.0f * (float)ia / (float)dh));
+    sincosf(pos * freq, &sn, &cs);
+  }
+  tab[id] = make_float2(cs, sn);
+}
+
+hipError_t launch_rope_table(void *tab, int rows, int n_text, int tok0, int grid_w, int dh, float theta, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  int64_t n = (int64_t)rows * (dh >> 1);
+  rope_table_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>((float2 *)tab, rows, n_text, tok0, grid_w, dh, theta);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint4 *p, size_t n16) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   size_t stride = (size_t)gridDim.x * 256;

@@ -1,13 +1,27 @@
 // GEMM epilogues shared by the SIMT and MFMA GEMM kernels.
 //   mode 0: C[row][col] (dtype) = acc + bias[col], GELU on columns >= gelu_from
 //   mode 1: X[row][col] (fp32)  = R[row][col] + gate[col] * (acc + bias[col]); optional rounded copy in C2
+// A mode-0 launch that is a QKV projection may carry a KvRoute: its k and v columns then go straight into a layer's
+// K / V^T buffers at the patch's rows (the write-before-attend step of PipeFusion Sec. 3.3) instead of into C, and
+// q and k are rotated with a precomputed (cos, sin) table when the stage uses RoPE.  Only the vectorised LDS-staged
+// epilogue of the direct-to-LDS GEMM kernels implements the route.
 #pragma once
 #include "common.h"
 
 namespace pf {
 
+// N = 3d columns: [0,d) q -> C, [d,2d) k -> kbuf[h][brow][c], [2d,3d) v -> vtbuf[h][c][brow].
+// GEMM row r maps to buffer row (r < split ? row0a + r : row0b + r - split): text rows first, then the image patch.
+struct KvRoute {
+  void *kbuf, *vtbuf;          // nullptr kbuf: no routing
+  int Lp, dh, d;
+  int split, row0a, row0b;
+  const float2 *rope;          // [M][dh/2] (cos, sin) per GEMM row, or nullptr
+};
+
 template <typename T>
 struct Epilogue {
+  KvRoute kv;
   const T *bias;
   void *C; int64_t ldc;
   int mode, gelu_from, gelu_tanh;
@@ -32,6 +46,8 @@ struct Epilogue {
 template <typename T, typename Args>
 inline Epilogue<T> make_epilogue(const Args &a) {
   Epilogue<T> e;
+  e.kv = KvRoute{a.kvr.kbuf, a.kvr.vtbuf, a.kvr.Lp, a.kvr.dh, a.kvr.d, a.kvr.split, a.kvr.row0a, a.kvr.row0b,
+                 (const float2 *)a.kvr.rope};
   e.bias = (const T *)a.bias; e.C = a.C; e.ldc = a.ldc; e.mode = a.epilogue; e.gelu_from = a.gelu_from;
   e.gelu_tanh = a.gelu_tanh; e.gate = a.gate; e.R = a.R; e.ldr = a.ldr; e.C2 = (T *)a.C2; e.ldc2 = a.ldc2;
   return e;

@@ -72,7 +72,32 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] += (float)b[e];
     }
-    if (epi.mode == 0) {
+    if (epi.mode == 0 && epi.kv.kbuf) {
+      // QKV projection routed into the K / V^T buffers (an 8-column group never straddles q|k|v or two heads)
+      const KvRoute &kv = epi.kv;
+      const int part = col / kv.d, cc = col - part * kv.d;
+      const int hh = cc / kv.dh, ch = cc - hh * kv.dh;
+      if (kv.rope && part < 2) {
+        const float2 *tab = kv.rope + (size_t)row * (kv.dh >> 1) + (ch >> 1);
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          float2 cs = tab[e >> 1];
+          float a0 = v[e], b0 = v[e + 1];
+          v[e] = a0 * cs.x - b0 * cs.y;
+          v[e + 1] = a0 * cs.y + b0 * cs.x;
+        }
+      }
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
+      if (part == 0) {
+        *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(epi.C) + (size_t)row * epi.ldc + col) = o;
+      } else if (part == 1) {
+        const int brow = row < kv.split ? kv.row0a + row : kv.row0b + (row - kv.split);
+        *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(kv.kbuf) + ((size_t)hh * kv.Lp + brow) * kv.dh + ch) = o;
+      }
+      // part 2 (v) is written by the transposed pass below
+    } else if (epi.mode == 0) {
       if (col + 8 > epi.gelu_from) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -103,6 +128,34 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = (bf16_t)x[e];
         *reinterpret_cast<bf16x8 *>(epi.C2 + (size_t)row * epi.ldc2 + col) = o;
+      }
+    }
+  }
+  // v columns of a routed QKV projection: V^T[h][c][buffer row].  The tile is walked column-wise, eight consecutive
+  // rows per thread and consecutive threads along the rows, so that the stores run along V^T's contiguous axis.
+  if (epi.mode == 0 && epi.kv.kbuf && n0 + BN > 2 * epi.kv.d) {
+    const KvRoute &kv = epi.kv;
+    constexpr int RG = BM / 8;
+    for (int u = threadIdx.x; u < RG * BN; u += NT) {
+      const int rg = u % RG, cl = u / RG;
+      const int col = n0 + cl, row = m0 + rg * 8;
+      if (col >= N || col < 2 * kv.d || row >= M) continue;
+      const int cc = col - 2 * kv.d;
+      const float b = epi.bias ? (float)epi.bias[col] : 0.f;
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(tile[(rg * 8 + e) * TLD + cl] + b);
+      bf16_t *vt = reinterpret_cast<bf16_t *>(kv.vtbuf) + (size_t)cc * kv.Lp;   // cc = h*dh + c
+      const int brow = row < kv.split ? kv.row0a + row : kv.row0b + (row - kv.split);
+      const bool whole = row + 8 <= M && (row >= kv.split || row + 8 <= kv.split);
+      if (whole && (brow & 7) == 0) {
+        *reinterpret_cast<bf16x8 *>(vt + brow) = o;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int r2 = row + e;
+          if (r2 < M) vt[r2 < kv.split ? kv.row0a + r2 : kv.row0b + (r2 - kv.split)] = o[e];
+        }
       }
     }
   }
@@ -412,6 +465,11 @@ hipError_t launch_wavek(const GemmArgs &a, hipStream_t s) {
 }
 
 }  // namespace
+
+bool gemm_kv_route_supported(const GemmArgs &a) {
+  return a.dt == DT_BF16 && a.path != PATH_SIMT && a.epilogue == 0 && a.K % BK == 0 && a.K >= BK && a.N % 8 == 0 &&
+         vec_epilogue_ok(a) && a.kvr.dh % 8 == 0 && a.kvr.d % 8 == 0 && a.N == 3 * a.kvr.d;
+}
 
 bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= BK && a.M >= 1 && a.N >= 1; }
 

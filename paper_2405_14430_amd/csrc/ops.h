@@ -31,6 +31,9 @@ hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *
                               float eps, void *out, int64_t ldo, int rows, int d, int normalize,
                               hipStream_t s);
 
+struct KvRoute;   // epilogue.h
+struct GemmArgsKv { void *kbuf, *vtbuf; int Lp, dh, d, split, row0a, row0b; const void *rope; };
+
 struct GemmArgs {
   int dt, path;
   const void *A; int64_t lda;
@@ -43,8 +46,14 @@ struct GemmArgs {
   const float *gate;   // [N] or nullptr
   const float *R; int64_t ldr;
   void *C2; int64_t ldc2;
+  GemmArgsKv kvr;      // kbuf == nullptr: plain GEMM
 };
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+bool gemm_kv_route_supported(const GemmArgs &a);   // the fused QKV -> K/V^T write needs the vectorised bf16 epilogue
+
+// (cos, sin) of the RoPE angles for the rows of a call: rows [0, n_text) are text (no rotation), row n_text + i is image
+// token tok0 + i on a grid of width grid_w.  tab is float2 [rows][dh/2].
+hipError_t launch_rope_table(void *tab, int rows, int n_text, int tok0, int grid_w, int dh, float theta, hipStream_t s);
 
 struct ScatterArgs {
   int dt;

@@ -14,9 +14,12 @@
 
 using namespace pf;
 
+static int g_fuse_kv_route = 1;   // tuning hook 200/201: K/V written by the QKV GEMM epilogue (1) or the scatter kernel (0)
+
 namespace {
 
 thread_local std::string g_create_error;
+
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -89,7 +92,7 @@ size_t kv_layer_bytes(const pf_config *c, const Derived &d) {
 }
 
 struct WsLayout {
-  size_t mod, xres, h, qkv, a, u, xb, qc, attn, total;
+  size_t mod, xres, h, qkv, a, u, xb, qc, rope, attn, total;
   size_t attn_bytes;
   int64_t lda_a;  // row stride of the attention-output buffer (d, or d+F for kind 3)
 };
@@ -116,6 +119,7 @@ WsLayout ws_layout(const pf_config *c, const Derived &d) {
     w.xb = take(R * D * e);
     w.qc = take(R * D * e);
   }
+  if (c->kind == PF_BLOCK_SINGLE_STREAM) w.rope = take(R * (size_t)(c->head_dim / 2) * 2 * sizeof(float));
   const int path = use_path(c);
   size_t ab = 0;
   // every query-row count a call can have: image-only patch, patch with the joint text rows, warm-up pass
@@ -196,8 +200,9 @@ hipError_t run(pf_stage *s, int cls, Fn &&fn) {
 
 hipError_t gemm(pf_stage *s, int cls, const void *A, int64_t lda, const void *W, int64_t ldw, const void *bias,
                 void *C, int64_t ldc, int M, int N, int K, int epilogue, int gelu_from, const float *gate,
-                const float *R, int64_t ldr, void *C2, int64_t ldc2) {
+                const float *R, int64_t ldr, void *C2, int64_t ldc2, const GemmArgsKv *kvr = nullptr) {
   GemmArgs g{};
+  if (kvr) g.kvr = *kvr;
   g.dt = s->cfg.dtype; g.path = use_path(&s->cfg);
   g.A = A; g.lda = lda; g.W = W; g.ldw = ldw; g.bias = bias; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.epilogue = epilogue; g.gelu_from = gelu_from; g.gelu_tanh = s->cfg.gelu_tanh; g.gate = gate; g.R = R; g.ldr = ldr;
@@ -226,6 +231,39 @@ hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const voi
   if (e != hipSuccess) return e;
   if (a.splits > 1) e = run(s, PF_KC_ATTN_COMBINE, [&] { return launch_attn_combine(a, s->stream); });
   return e;
+}
+
+// QKV projection of `rows` rows plus the write of their K/V into the layer's buffers (buffer row of GEMM row r:
+// r < split ? row0a + r : row0b + r - split).  When the bf16 GEMM's vectorised epilogue can do it, k and v go straight
+// from the accumulators into K / V^T (q, and RoPE through `rope_tab`, likewise); otherwise the projection lands in the
+// qkv workspace and the scatter kernel moves (and rotates) it.
+pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, char *qs, int rows, char *kb, char *vb,
+                      int split, int row0a, int row0b, const void *rope_tab, int tok0) {
+  const pf_config &c = s->cfg;
+  const Derived &d = s->d;
+  const int D = c.hidden;
+  const bool rope = c.kind == PF_BLOCK_SINGLE_STREAM;
+  GemmArgsKv kvr{kb, vb, d.Lp, c.head_dim, D, split, row0a, row0b, rope ? rope_tab : nullptr};
+  GemmArgs probe{};
+  probe.dt = c.dtype; probe.path = use_path(&c); probe.A = hs; probe.lda = D; probe.W = lw.w_qkv; probe.ldw = D;
+  probe.bias = lw.b_qkv; probe.C = qs; probe.ldc = 3 * D; probe.M = rows; probe.N = 3 * D; probe.K = D; probe.epilogue = 0;
+  probe.gelu_from = 3 * D; probe.kvr = kvr;
+  if (g_fuse_kv_route && gemm_kv_route_supported(probe)) {
+    PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, lw.w_qkv, D, lw.b_qkv, qs, 3 * D, rows, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0,
+                nullptr, 0, &kvr));
+    return PF_OK;
+  }
+  PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, lw.w_qkv, D, lw.b_qkv, qs, 3 * D, rows, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0,
+              nullptr, 0));
+  hipStream_t st = s->stream;
+  if (split > 0) {
+    ScatterArgs sa{c.dtype, qs, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, row0a, split, rope ? 1 : 0, -1, c.grid_w, c.rope_theta};
+    PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+  }
+  ScatterArgs sb{c.dtype, qs + (size_t)split * 3 * D * d.esz, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, row0b, rows - split,
+                 rope ? 1 : 0, tok0, c.grid_w, c.rope_theta};
+  PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sb, st); }));
+  return PF_OK;
 }
 
 // The block stack on image rows [img_off, img_off + n_img) and, for the joint kinds, on the T text rows when
@@ -280,19 +318,20 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
   }
 
   const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
+  if (c.kind == PF_BLOCK_SINGLE_STREAM)    // (cos, sin) of every row's RoPE angles, shared by all layers of the call
+    PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_rope_table(ws + w.rope, R, Tt, img_off, c.grid_w, c.head_dim, c.rope_theta, st); }));
   for (int l = 0; l < c.n_layers; ++l) {
     char *kb = s->kptr(l), *vb = s->vptr(l);
     if (c.kind == PF_BLOCK_SINGLE_STREAM) {
       const pf_layer_weights &lw = s->img[l];
       const float *m = s->mod(0, l);
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xsrc, D, m, m + D, c.ln_eps, h, D, R, D, 1, st); }));
-      PF_TRY(gemm(s, PF_KC_GEMM_QKV, h, D, lw.w_qkv, D, lw.b_qkv, qkv, 3 * D, R, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0, nullptr, 0));
+      {
+        pf_status qs_ = qkv_project(s, h, lw, qkv, R, kb, vb, Tt, 0, row0_img, ws + w.rope, img_off);
+        if (qs_ != PF_OK) return qs_;
+      }
       // MLP branch runs in parallel with attention: GELU(h W_up^T + b) lands right of the attention columns
       PF_TRY(gemm(s, PF_KC_GEMM_UP, h, D, lw.w_up, D, lw.b_up, a + (size_t)D * e, D + F, R, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
-      ScatterArgs sa{dt, qkv, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, 0, Tt, 1, -1, c.grid_w, c.rope_theta};
-      if (Tt) PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
-      sa.qkv = qkv + (size_t)Tt * 3 * D * e; sa.row0 = row0_img; sa.rows = n_img; sa.tok0 = img_off;
-      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
       PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D + F, R));
       PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xbuf, D, R, D, D + F, 1, 0, m + 2 * D, xsrc, D, nullptr, 0));
       xsrc = xbuf;
@@ -312,9 +351,8 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       char *hs = h + (size_t)sm.r0 * D * e;
       char *qs = qkv + (size_t)sm.r0 * 3 * D * e;
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, sm.nr, D, 1, st); }));
-      PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, sm.lw->w_qkv, D, sm.lw->b_qkv, qs, 3 * D, sm.nr, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0, nullptr, 0));
-      ScatterArgs sa{dt, qs, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, sm.brow0, sm.nr, 0, -1, c.grid_w, c.rope_theta};
-      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+      pf_status qs_ = qkv_project(s, hs, *sm.lw, qs, sm.nr, kb, vb, 0, 0, sm.brow0, nullptr, -1);
+      if (qs_ != PF_OK) return qs_;
     }
     PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R));
     for (int si = 0; si < ns; ++si) {
@@ -603,7 +641,9 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 namespace pf { extern int g_gemm_tile_override; }
 namespace pf { extern int g_attn_variant; }
 extern "C" void pf_tune_gemm_tile(int id) {
-  if (id >= 100) pf::g_attn_variant = id - 100; else pf::g_gemm_tile_override = id;
+  if (id >= 200) g_fuse_kv_route = id - 200;
+  else if (id >= 100) pf::g_attn_variant = id - 100;
+  else pf::g_gemm_tile_override = id;
 }
 
 namespace pf {
