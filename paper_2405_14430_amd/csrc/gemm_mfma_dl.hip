@@ -164,17 +164,21 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
 // ------------------------------------------------------------------------------------------------------------------
 // WGM x WGN wavefronts on one shared tile
 // ------------------------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2>
+template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2, int KB = 64>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t *__restrict__ A, int64_t lda,
                                                         const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
                                                         Epilogue<bf16_t> epi, int vec_ok, int n_major) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int MI = WM / 32, NI = WN / 32;
-  constexpr int LA = BM / 8 / NW, LW = BN / 8 / NW;  // load instructions per wave per stage
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split evenly over the waves' load instructions");
+  // KB = K elements per stage: 64 (128-byte tile rows, 8 rows per load instruction, swizzle key (r>>1)&7) or
+  // 32 (64-byte rows, 16 rows per instruction, key (r>>2)&3: sixteen consecutive rows then cover all 64 banks)
+  constexpr int RBY = KB * 2, RPI = 1024 / RBY, CPR = KB / 8;
+  constexpr int LA = BM / RPI / NW, LW = BN / RPI / NW;  // load instructions per wave per stage
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split evenly over the waves' load instructions");
   constexpr int LPS = LA + LW;
-  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  constexpr int STAGE_BYTES = (BM + BN) * RBY;
+  auto key = [](int r) { return KB == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
   constexpr int TLD = BN + 4;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -190,20 +194,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
   const bf16_t *pw[LW];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
-    int r = (i * NW + wave) * 8 + (lane >> 3);
-    int c = (lane & 7) ^ ((r >> 1) & 7);
+    int r = (i * NW + wave) * RPI + lane / CPR;
+    int c = (lane % CPR) ^ key(r);
     pa[i] = A + (size_t)min(m0 + r, M - 1) * lda + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
-    int r = (i * NW + wave) * 8 + (lane >> 3);
-    int c = (lane & 7) ^ ((r >> 1) & 7);
+    int r = (i * NW + wave) * RPI + lane / CPR;
+    int c = (lane % CPR) ^ key(r);
     pw[i] = W + (size_t)min(n0 + r, N - 1) * ldw + c * 8;
   }
   auto issue = [&](int stage, int kt) {
     unsigned char *sa = smem + stage * STAGE_BYTES;
-    unsigned char *sw = sa + BM * ROW_BYTES;
-    const int koff = kt * BK;
+    unsigned char *sw = sa + BM * RBY;
+    const int koff = kt * KB;
 #pragma unroll
     for (int i = 0; i < LA; ++i) lds_load16(pa[i] + koff, sa + (i * NW + wave) * 1024);
 #pragma unroll
@@ -218,7 +222,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / BK;
+  const int nk = K / KB;
 #pragma unroll
   for (int s = 0; s < NSTAGE - 1; ++s)
     if (s < nk) issue(s, s);
@@ -228,14 +232,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     int r = wm * WM + i * 32 + l32;
-    arow[i] = r * ROW_BYTES;
-    akey[i] = (r >> 1) & 7;
+    arow[i] = r * RBY;
+    akey[i] = key(r);
   }
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     int r = wn * WN + j * 32 + l32;
-    wrow[j] = BM * ROW_BYTES + r * ROW_BYTES;
-    wkey[j] = (r >> 1) & 7;
+    wrow[j] = BM * RBY + r * RBY;
+    wkey[j] = key(r);
   }
 
   for (int kt = 0; kt < nk; ++kt) {
@@ -251,7 +255,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
     const unsigned char *st = smem + (kt % NSTAGE) * STAGE_BYTES;
     // Fragments are read from LDS PRE k-steps ahead of the MFMAs that use them: with one accumulator per wave
     // (64x64 tile) a k-step is a single MFMA, far shorter than an LDS read, so the whole tile is preloaded.
-    constexpr int KS = BK / 16;
+    constexpr int KS = KB / 16;
     constexpr int PRE = (MI * NI <= 2) ? KS : 2;
     bf16x8 af[PRE][MI], wf[PRE][NI];
     auto lread = [&](int buf, int ks) {
@@ -266,6 +270,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (ks + PRE - 1 < KS) lread((ks + PRE - 1) % PRE, ks + PRE - 1);
+      // keep the LDS reads of the next k-step ahead of this k-step's MFMAs (the scheduler would otherwise sink them
+      // to reuse the fragment registers, exposing the LDS latency at every k-step)
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -427,21 +434,21 @@ bool vec_epilogue_ok(const GemmArgs &a) {
   return ok;
 }
 
-template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2>
+template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2, int KB = 64>
 hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
   // the stage ring, or the fp32 tile (row stride BN + 4) that replaces it for the epilogue, whichever is larger
-  constexpr int ring = NSTAGE * (BM + BN) * ROW_BYTES, tile = BM * (BN + 4) * 4;
+  constexpr int ring = NSTAGE * (BM + BN) * KB * 2, tile = BM * (BN + 4) * 4;
   constexpr int smem = (tile > ring && tile <= 96 * 1024) ? tile : ring;   // larger tiles finish in row passes
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int64_t T = (int64_t)((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
   dim3 g((unsigned)(((T + 7) / 8) * 8));
-  gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
+  gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
                                                        a.K, make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0,
                                                        a.N >= a.M ? 1 : 0);
   return hipGetLastError();
@@ -495,6 +502,13 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 16: return launch_tile<128, 256, 3, 2, 4>(a, s);
     case 17: return launch_tile<256, 128, 2, 4, 2>(a, s);
     case 18: return launch_tile<256, 256, 2, 2, 2>(a, s);
+    case 19: return launch_tile<128, 128, 2, 2, 2, 32>(a, s);
+    case 20: return launch_tile<128, 128, 3, 2, 2, 32>(a, s);
+    case 21: return launch_tile<128, 128, 4, 2, 2, 32>(a, s);
+    case 22: return launch_tile<256, 128, 3, 4, 2, 32>(a, s);
+    case 23: return launch_tile<256, 128, 4, 4, 2, 32>(a, s);
+    case 24: return launch_tile<256, 256, 3, 4, 2, 32>(a, s);
+    case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
     default: break;
   }
   auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
