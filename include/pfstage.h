@@ -249,6 +249,10 @@ pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void
                      int gelu_from, int gelu_tanh, const float *gate, const float *R, int64_t ldr,
                      void *C2, int64_t ldc2, void *stream);
 
+/* Name of the kernel instance the library's tile heuristic runs for a GEMM of this shape (static string; matches the
+ * template instance seen in a rocprofv3 kernel trace).  Used by the benchmark to group GEMM launches by kernel. */
+const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K);
+
 /*
  * Write rows of fresh keys/values into a layer's buffer.  qkv dtype [rows, 3d] (row stride ld): q | k | v.
  * Row i goes to buffer row row0 + i of K [H][rows_padded][dh] and of V^T [H][dh][rows_padded]; no other

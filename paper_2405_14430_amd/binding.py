@@ -54,7 +54,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention",
-           "pf_tune_gemm_tile"]
+           "pf_tune_gemm_tile", "pf_gemm_kernel_name"]
 
 _lib = None
 
@@ -110,6 +110,8 @@ def load_library():
     lib.pf_op_attention_ws_bytes.argtypes = [i32, i32, i32, i32]
     lib.pf_op_attention.restype = i32
     lib.pf_op_attention.argtypes = [i32, i32, vp, i64, vp, vp, i32, i32, i32, i32, vp, i64, i32, i32, vp, sz, vp]
+    lib.pf_gemm_kernel_name.restype = C.c_char_p
+    lib.pf_gemm_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.pf_tune_gemm_tile.restype = None
     lib.pf_tune_gemm_tile.argtypes = [i32]
     _lib = lib

@@ -482,6 +482,19 @@ bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= 
 
 int g_gemm_tile_override = 0;   // tuning hook: 0 = heuristic, 1.. = a fixed tile configuration
 
+// Tile heuristic.  Measured on MI355X: the 8-wave 256x256 / 256x128 tiles need the fewest L1 bytes per flop and win once
+// they fill the chip for several rounds; 128x128 (two workgroups per CU) from about 1.5 workgroups per CU; below that
+// the 64x64 tile, and the K-splitting kernel when K is long and tiles are few.
+static int pick_variant(const GemmArgs &a) {
+  auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+  if (tiles(256, 256) >= 1024) return 0;
+  if (tiles(256, 128) >= 512) return 1;
+  if (tiles(128, 128) >= 384) return 2;
+  if (tiles(128, 64) >= 512) return 3;
+  if (tiles(64, 64) < 512 && a.K >= 2048) return 4;
+  return 5;
+}
+
 hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
   switch (g_gemm_tile_override) {
     case 1: return launch_tile<256, 128, 3>(a, s);
@@ -511,15 +524,21 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
     default: break;
   }
-  auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-  // Measured on MI355X: 128x128 (two workgroups per CU) is the fastest tile once it yields >= 1.5 workgroups per CU;
-  // below that the 64x64 tile wins, and when K is long and tiles are few the K-splitting kernel does.
-  if (tiles(256, 256) >= 1024) return launch_tile<256, 256, 2, 4, 2>(a, s);   // 8 waves, least L1 traffic per flop
-  if (tiles(256, 128) >= 512) return launch_tile<256, 128, 2, 4, 2>(a, s);
-  if (tiles(128, 128) >= 384) return launch_tile<128, 128, 2>(a, s);
-  if (tiles(128, 64) >= 512) return launch_tile<128, 64, 2>(a, s);
-  if (tiles(64, 64) < 512 && a.K >= 2048) return launch_wavek<64, 64>(a, s);
-  return launch_tile<64, 64, 2>(a, s);
+  switch (pick_variant(a)) {
+    case 0: return launch_tile<256, 256, 2, 4, 2>(a, s);
+    case 1: return launch_tile<256, 128, 2, 4, 2>(a, s);
+    case 2: return launch_tile<128, 128, 2>(a, s);
+    case 3: return launch_tile<128, 64, 2>(a, s);
+    case 4: return launch_wavek<64, 64>(a, s);
+    default: return launch_tile<64, 64, 2>(a, s);
+  }
+}
+
+const char *gemm_mfma_dl_variant_name(const GemmArgs &a) {
+  static const char *names[] = {"gemm_tile_kernel<256,256,2,4,2,64>", "gemm_tile_kernel<256,128,2,4,2,64>",
+                                "gemm_tile_kernel<128,128,2,2,2,64>", "gemm_tile_kernel<128,64,2,2,2,64>",
+                                "gemm_wavek_kernel<64,64>", "gemm_tile_kernel<64,64,2,2,2,64>"};
+  return names[pick_variant(a)];
 }
 
 }  // namespace pf

@@ -83,6 +83,7 @@ hipError_t launch_gemm_simt(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);
 bool gemm_mfma_dl_supported(const GemmArgs &a);            // direct-to-LDS multi-stage variant (K % 64 == 0)
 hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s);
+const char *gemm_mfma_dl_variant_name(const GemmArgs &a);   // kernel instance the tile heuristic picks for this shape
 hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
 bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS variant for head sizes 64 / 72 / 128

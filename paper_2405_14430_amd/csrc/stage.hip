@@ -625,6 +625,13 @@ pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *v
   return launch_kv_scatter(sa, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 
+const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K) {
+  GemmArgs g{};
+  g.dt = dtype; g.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT; g.M = M; g.N = N; g.K = K;
+  if (g.path == PATH_SIMT || dtype != PF_BF16) return "gemm_simt_kernel";
+  return gemm_mfma_dl_supported(g) ? gemm_mfma_dl_variant_name(g) : "gemm_mfma_kernel";
+}
+
 size_t pf_op_attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
   return attention_ws_bytes(nq, n_heads, head_dim, splits);
 }
