@@ -482,17 +482,28 @@ bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= 
 
 int g_gemm_tile_override = 0;   // tuning hook: 0 = heuristic, 1.. = a fixed tile configuration
 
-// Tile heuristic.  Measured on MI355X: the 8-wave 256x256 / 256x128 tiles need the fewest L1 bytes per flop and win once
-// they fill the chip for several rounds; 128x128 (two workgroups per CU) from about 1.5 workgroups per CU; below that
-// the 64x64 tile, and the K-splitting kernel when K is long and tiles are few.
+// Tile heuristic, from A/B runs inside the stage on MI355X (weights come from HBM there, not from a warm L2, which
+// favours deeper rings than an isolated GEMM loop suggests):
+//  * the 8-wave 256x256 / 256x128 tiles need the fewest L1 bytes per flop and win once they fill the chip;
+//    256x128 runs best with 32-wide K stages and three of them; long-K GEMMs with few tiles (Flux-scale MLP-down:
+//    192 tiles, K = 15360) prefer it too, with 64-wide stages;
+//  * 128x128 (two workgroups per CU) from about 1.5 workgroups per CU, then 128x64;
+//  * skinny GEMMs (n = 512 patch rows): 64x64 tiles with the deepest ring that still lets every workgroup be resident
+//    at once (4 stages: 2 per CU, 3 stages: 3 per CU), and the K-splitting kernel when K is long and tiles are few.
+enum { V_256x256 = 0, V_256x128_K32S3, V_256x128_S3, V_128x128, V_128x64, V_WAVEK, V_64x64_S4, V_64x64_S3, V_64x64_S2, V_COUNT };
+
 static int pick_variant(const GemmArgs &a) {
   auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-  if (tiles(256, 256) >= 1024) return 0;
-  if (tiles(256, 128) >= 512) return 1;
-  if (tiles(128, 128) >= 384) return 2;
-  if (tiles(128, 64) >= 512) return 3;
-  if (tiles(64, 64) < 512 && a.K >= 2048) return 4;
-  return 5;
+  if (tiles(256, 256) >= 1024) return V_256x256;
+  if (tiles(256, 128) >= 512) return V_256x128_K32S3;
+  if (a.K >= 8192 && tiles(256, 128) >= 128) return V_256x128_S3;
+  if (tiles(128, 128) >= 384) return V_128x128;
+  if (tiles(128, 64) >= 512) return V_128x64;
+  const int64_t t64 = tiles(64, 64);
+  if (t64 < 512 && a.K >= 2048) return V_WAVEK;
+  if (t64 <= 512) return V_64x64_S4;
+  if (t64 <= 768) return V_64x64_S3;
+  return V_64x64_S2;
 }
 
 hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
@@ -522,22 +533,29 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 23: return launch_tile<256, 128, 4, 4, 2, 32>(a, s);
     case 24: return launch_tile<256, 256, 3, 4, 2, 32>(a, s);
     case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
+    case 26: return launch_tile<64, 64, 3>(a, s);
+    case 27: return launch_tile<128, 64, 3>(a, s);
     default: break;
   }
   switch (pick_variant(a)) {
-    case 0: return launch_tile<256, 256, 2, 4, 2>(a, s);
-    case 1: return launch_tile<256, 128, 2, 4, 2>(a, s);
-    case 2: return launch_tile<128, 128, 2>(a, s);
-    case 3: return launch_tile<128, 64, 2>(a, s);
-    case 4: return launch_wavek<64, 64>(a, s);
+    case V_256x256: return launch_tile<256, 256, 2, 4, 2>(a, s);
+    case V_256x128_K32S3: return launch_tile<256, 128, 3, 4, 2, 32>(a, s);
+    case V_256x128_S3: return launch_tile<256, 128, 3, 4, 2>(a, s);
+    case V_128x128: return launch_tile<128, 128, 2>(a, s);
+    case V_128x64: return launch_tile<128, 64, 2>(a, s);
+    case V_WAVEK: return launch_wavek<64, 64>(a, s);
+    case V_64x64_S4: return launch_tile<64, 64, 4>(a, s);
+    case V_64x64_S3: return launch_tile<64, 64, 3>(a, s);
     default: return launch_tile<64, 64, 2>(a, s);
   }
 }
 
 const char *gemm_mfma_dl_variant_name(const GemmArgs &a) {
-  static const char *names[] = {"gemm_tile_kernel<256,256,2,4,2,64>", "gemm_tile_kernel<256,128,2,4,2,64>",
-                                "gemm_tile_kernel<128,128,2,2,2,64>", "gemm_tile_kernel<128,64,2,2,2,64>",
-                                "gemm_wavek_kernel<64,64>", "gemm_tile_kernel<64,64,2,2,2,64>"};
+  static const char *names[V_COUNT] = {"gemm_tile_kernel<256,256,2,4,2,64>", "gemm_tile_kernel<256,128,3,4,2,32>",
+                                       "gemm_tile_kernel<256,128,3,4,2,64>", "gemm_tile_kernel<128,128,2,2,2,64>",
+                                       "gemm_tile_kernel<128,64,2,2,2,64>", "gemm_wavek_kernel<64,64>",
+                                       "gemm_tile_kernel<64,64,4,2,2,64>", "gemm_tile_kernel<64,64,3,2,2,64>",
+                                       "gemm_tile_kernel<64,64,2,2,2,64>"};
   return names[pick_variant(a)];
 }
 
