@@ -8,8 +8,8 @@
 // so the online-softmax statistics are in-lane reductions plus one exchange with lane^32 and the O^T rescale is per lane.
 //
 // K tiles ([64 kv][dh], contiguous in the head-major buffer) and V^T tiles ([dh][64 kv]) come in with
-// global_load_lds_dwordx4 into a two-stage LDS ring (one s_barrier per tile, prefetch of tile t+1 in flight during tile
-// t).  The LDS side of those loads is lane-linear, so bank conflicts are handled by XOR-swizzling the 16-byte chunks of a
+// global_load_lds_dwordx4 into a two- or three-stage LDS ring (one s_barrier per tile, the next one or two tiles in flight
+// during tile t).  The LDS side of those loads is lane-linear, so bank conflicts are handled by XOR-swizzling the 16-byte chunks of a
 // row (the loading lane fetches the chunk that belongs at its LDS slot); dh = 72 rows are 144 bytes, which is conflict
 // free without a swizzle.  Before the PV product the two half-waves exchange half of their packed P registers
 // (v_permlane32_swap) so that each lane's eight P values cover eight CONSECUTIVE kv rows; the matching V^T operand is
@@ -60,7 +60,7 @@ struct Cfg {
   }
 };
 
-template <int DH>
+template <int DH, int NS>
 __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__restrict__ q, int64_t ldq,
                                                             const bf16_t *__restrict__ kbuf,
                                                             const bf16_t *__restrict__ vtbuf, int kv_rows, int Lp, int H,
@@ -84,10 +84,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   const int qt = rem / splits, sp = rem - qt * splits;
   const int q0 = qt * TQ + wave * 32;
 
-  // ---- zero the V^T padding rows (never written by the tile loads) of both stages
+  // ---- zero the V^T padding rows (never written by the tile loads) of every stage
   if constexpr (C::V_ROWS > DH) {
     constexpr int PADB = (C::V_ROWS - DH) * 128;
-    for (int e = tid; e < 2 * PADB / 16; e += 256) {
+    for (int e = tid; e < NS * PADB / 16; e += 256) {
       int st = e / (PADB / 16), o = e % (PADB / 16);
       *reinterpret_cast<uint4 *>(smem + st * C::STAGE + C::K_BYTES + DH * 128 + o * 16) = make_uint4(0, 0, 0, 0);
     }
@@ -127,7 +127,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
 #pragma unroll
     for (int i = 0; i < C::LV; ++i) lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
   };
-  if (t_begin < t_end) issue(0, t_begin);
+#pragma unroll
+  for (int i = 0; i < NS - 1; ++i)
+    if (t_begin + i < t_end) issue(i, t_begin + i);
 
   // ---- Q fragments (B operand): lane holds query q0 + l32, channels ks*16 + 8*hi .. +7
   bf16x8 qf[C::KS16];
@@ -177,10 +179,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
 
   auto tile_step = [&](int t, auto stage_c) {
     constexpr int stage = decltype(stage_c)::value;
-    wait_vmcnt<0>();                      // tile t (the only one in flight for this wave) has landed
-    __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the other stage
+    // tile t has landed once at most min(NS-2, tiles left after t) later tiles of this wave are still in flight
+    if (NS >= 3 && t + 1 < t_end) wait_vmcnt<(NS >= 3 ? C::LPS : 0)>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the stage of tile t-1
     asm volatile("" ::: "memory");
-    if (t + 1 < t_end) issue(stage ^ 1, t + 1);
+    if (t + NS - 1 < t_end) issue((stage + NS - 1) % NS, t + NS - 1);
     const unsigned char *st = smem + stage * C::STAGE;
 
     // ---- S^T = K . Q^T for the two 32-row blocks of the tile
@@ -262,9 +265,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
         }
     }
   };
-  for (int t = t_begin; t < t_end; t += 2) {
+  for (int t = t_begin; t < t_end; t += NS) {
     tile_step(t, std::integral_constant<int, 0>{});
     if (t + 1 < t_end) tile_step(t + 1, std::integral_constant<int, 1>{});
+    if constexpr (NS >= 3) {
+      if (t + 2 < t_end) tile_step(t + 2, std::integral_constant<int, 2>{});
+    }
   }
   wait_vmcnt<0>();
 
@@ -307,20 +313,20 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   }
 }
 
-template <int DH>
+template <int DH, int NS>
 hipError_t launch2(const AttnArgs &a, hipStream_t s) {
   using C = Cfg<DH>;
-  constexpr int smem = 2 * C::STAGE;
+  constexpr int smem = NS * C::STAGE;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH, NS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int qtiles = (a.nq + TQ - 1) / TQ;
   dim3 g(qtiles * a.n_heads * a.splits);
-  attn_mfma2_kernel<DH><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
+  attn_mfma2_kernel<DH, NS><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
                                              a.kv_rows, a.rows_padded, a.n_heads, (bf16_t *)a.out, a.ldo, a.nq, a.splits,
                                              qtiles, a.ws);
   return hipGetLastError();
@@ -332,11 +338,16 @@ bool attn_mfma2_supported(const AttnArgs &a) {
   return (a.head_dim == 64 || a.head_dim == 72 || a.head_dim == 128) && a.rows_padded % TK == 0;
 }
 
+int g_attn_stages = 0;   // tuning hook: 0 = default ring depth, 2 / 3 = forced
+
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s) {
   if (a.nq <= 0) return hipSuccess;
-  if (a.head_dim == 64) return launch2<64>(a, s);
-  if (a.head_dim == 72) return launch2<72>(a, s);
-  return launch2<128>(a, s);
+  // Two stages by default: in-stage A/B runs on MI355X showed no gain from a third stage for dh = 64 / 72 (1626 vs
+  // 1635 us on the 64K-key PixArt stage) and a loss for dh = 128, where it halves the workgroups per CU (430 vs 565 us).
+  const int ns = g_attn_stages ? g_attn_stages : 2;
+  if (a.head_dim == 64) return ns == 3 ? launch2<64, 3>(a, s) : launch2<64, 2>(a, s);
+  if (a.head_dim == 72) return ns == 3 ? launch2<72, 3>(a, s) : launch2<72, 2>(a, s);
+  return ns == 3 ? launch2<128, 3>(a, s) : launch2<128, 2>(a, s);
 }
 
 }  // namespace pf
