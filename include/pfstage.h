@@ -249,6 +249,11 @@ pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void
                      int gelu_from, int gelu_tanh, const float *gate, const float *R, int64_t ldr,
                      void *C2, int64_t ldc2, void *stream);
 
+/* out[i] = x[i] + alpha * y[i] for i < n (float, device; out may alias x): the element-wise sampler update that sits
+ * between the last stage of diffusion step t and the first stage of step t-1 (Sec. 2, Eq. 1; Euler form).  n = 0 is a
+ * no-op (pointers may then be NULL); n < 0 gives PF_ERR_SHAPE, a NULL pointer with n > 0 PF_ERR_NULL. */
+pf_status pf_op_axpy(const float *x, const float *y, float alpha, float *out, int64_t n, void *stream);
+
 /* Name of the kernel instance the library's tile heuristic runs for a GEMM of this shape (static string; matches the
  * template instance seen in a rocprofv3 kernel trace).  Used by the benchmark to group GEMM launches by kernel. */
 const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K);

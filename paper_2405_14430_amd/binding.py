@@ -54,7 +54,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention",
-           "pf_tune_gemm_tile", "pf_gemm_kernel_name"]
+           "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy"]
 
 _lib = None
 
@@ -112,6 +112,8 @@ def load_library():
     lib.pf_op_attention.argtypes = [i32, i32, vp, i64, vp, vp, i32, i32, i32, i32, vp, i64, i32, i32, vp, sz, vp]
     lib.pf_gemm_kernel_name.restype = C.c_char_p
     lib.pf_gemm_kernel_name.argtypes = [i32, i32, i32, i32, i32]
+    lib.pf_op_axpy.restype = i32
+    lib.pf_op_axpy.argtypes = [vp, vp, f32, vp, i64, vp]
     lib.pf_tune_gemm_tile.restype = None
     lib.pf_tune_gemm_tile.argtypes = [i32]
     _lib = lib
@@ -322,4 +324,11 @@ def pf_op_attention(q, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, spl
     ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=q.device)
     _ok(lib.pf_op_attention(_dt_code(q), path, _ptr(q), q.stride(0), _ptr(kbuf), _ptr(vtbuf), kv_rows, rows_padded,
                             n_heads, head_dim, _ptr(out), out.stride(0), nq, splits, _ptr(ws), wsb, _stream_ptr()))
+    return out
+
+
+def pf_op_axpy(x, y, alpha, out=None):
+    lib = load_library()
+    out = torch.empty_like(x) if out is None else out
+    _ok(lib.pf_op_axpy(_ptr(x), _ptr(y), float(alpha), _ptr(out), x.numel(), _stream_ptr()))
     return out

@@ -625,6 +625,13 @@ pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *v
   return launch_kv_scatter(sa, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 
+pf_status pf_op_axpy(const float *x, const float *y, float alpha, float *out, int64_t n, void *stream) {
+  if (n < 0) return PF_ERR_SHAPE;
+  if (n == 0) return PF_OK;
+  if (!x || !y || !out) return PF_ERR_NULL;
+  return launch_axpy(x, y, alpha, out, n, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
 const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K) {
   GemmArgs g{};
   g.dt = dtype; g.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT; g.M = M; g.N = N; g.K = K;

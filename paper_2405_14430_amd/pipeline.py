@@ -1,0 +1,73 @@
+"""The PipeFusion sampling loop (Sec. 3.3) run on ONE device: N stage objects chained, M patches, S steps.
+
+Host orchestration only: every arithmetic step is a library call (pf_kv_init, pf_stage_patch_forward, pf_op_axpy).
+On N devices, device i would hold stage i and run item k = (step, patch) at micro-step k + i; a stage's K/V buffer only
+changes through its own calls, which arrive in the order of k, so running the items back to back here gives the same
+values as the N-device schedule (only the P2P transfers between stages are missing).
+"""
+from __future__ import annotations
+
+import torch
+
+from .binding import Stage, pf_op_axpy
+
+
+class Pipeline:
+    """stage_layers: one list of layer-weight dicts per stage.  All tensors passed in live on the device:
+    x [L, d] float32, cond float32, joint-kind text rows float32, kind-1 text features in the stage dtype."""
+
+    def __init__(self, cfg, stage_layers, kernel_path=0, device="cuda"):
+        self.cfg = dict(cfg)
+        self.stages = [Stage(cfg, layers, kernel_path=kernel_path, device=device) for layers in stage_layers]
+        self.N = len(self.stages)
+        self.M = int(cfg["n_patches"])
+        self.L = int(cfg["seq_img"])
+        self.n = self.L // self.M
+        self.d = int(cfg["hidden"])
+        self.joint = int(cfg["kind"]) in (2, 3)
+        f32 = dict(dtype=torch.float32, device=device)
+        # ping-pong hidden-state rows between consecutive stages (what P2P would carry), allocated once
+        self._h = [torch.empty(self.n, self.d, **f32) for _ in range(2)]
+        T = int(cfg.get("text_len", 0)) if self.joint else 0
+        self._t = [torch.empty(T, self.d, **f32) for _ in range(2)] if T else None
+        self.eps = torch.empty(self.L, self.d, **f32)
+
+    def warmup_step(self, x, cond, text=None):
+        """Synchronous step (Sec. 3.3 warm-up): full sequence through every stage; fills every K/V buffer.  Returns eps."""
+        h, ht = x, text
+        for st in self.stages:
+            if self.joint:
+                h, ht = st.kv_init(h, cond, ht, want_output=True)
+            else:
+                h, _ = st.kv_init(h, cond, text, want_output=True)
+        self.eps.copy_(h)
+        return self.eps
+
+    def pipelined_step(self, x, cond, text=None):
+        """One step after warm-up.  eps rows of patch p are written straight into self.eps by the last stage."""
+        n = self.n
+        for p in range(self.M):
+            src = x[p * n:(p + 1) * n]
+            tsrc = text if (self.joint and p == 0 and text is not None) else None
+            for i, st in enumerate(self.stages):
+                dst = self.eps[p * n:(p + 1) * n] if i == self.N - 1 else self._h[i & 1]
+                if tsrc is not None:
+                    st.patch_forward(src, cond, p, text=tsrc, out=dst, text_out=self._t[i & 1])
+                    tsrc = self._t[i & 1]
+                else:
+                    st.patch_forward(src, cond, p, out=dst)
+                src = dst
+        return self.eps
+
+    def run(self, x_T, conds, dts, warmup_steps=1, text=None):
+        """S = len(conds) steps, the first `warmup_steps` synchronous; Euler update x += dt * eps after each (Sec. 2, Eq. 1).
+        Returns x_0 (a new tensor; x_T is left untouched)."""
+        x = x_T.clone()
+        for s, (c, dt) in enumerate(zip(conds, dts)):
+            eps = self.warmup_step(x, c, text) if s < warmup_steps else self.pipelined_step(x, c, text)
+            pf_op_axpy(x, eps, dt, out=x)
+        return x
+
+    def destroy(self):
+        for st in self.stages:
+            st.destroy()

@@ -1,0 +1,150 @@
+"""Pins for the sampling-loop oracle (oracle/pf_pipeline.py), against things other than itself:
+the exact model written with torch.nn.functional (M = 1, all-warm-up), an emulation of the N-device micro-step
+schedule of PipeFusion Sec. 3.3 / Fig. 4 that issues the stage calls in device-time order, and the efficiency value
+the paper prints.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import pf_oracle as po
+from oracle import pf_pipeline as pp
+from full_forward_ref import full_forward
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+FP32_TWINS = ["K0f", "K1f", "K2f", "K3f"]
+
+
+def _rel(a, b):
+    return float(np.max(np.abs(a - b)) / (np.sqrt(np.mean(b ** 2)) + 1e-300))
+
+
+def _setup(name, n_stages=2, steps=3, **kw):
+    cfg = wl.variant(wl.CONFIGS[name], **kw) if kw else wl.CONFIGS[name]
+    W = wl.make_weights(cfg, n_layers=n_stages * cfg["n_layers"])
+    A = wl.make_activations(cfg)
+    conds, dts = wl.make_sampling(cfg, steps)
+    return cfg, W, A, conds, dts
+
+
+def _exact_loop(cfg, W, x, conds, dts, text):
+    """The original (single-device, no patches) sampler: full forward of all layers, then x += dt * eps."""
+    x = np.array(x, np.float64)
+    for c, dt in zip(conds, dts):
+        eps, _ = full_forward(cfg, W, x, c, text)
+        x = x + dt * eps
+    return x
+
+
+@pytest.mark.parametrize("name", FP32_TWINS)
+def test_one_patch_is_the_exact_sampler(name):
+    cfg, W, A, conds, dts = _setup(name, n_patches=1)
+    pipe = pp.PipelineOracle(cfg, wl.split_stages(W, 2))
+    got, _ = pipe.run(A["x"], conds, dts, warmup_steps=1, text=A["text"])
+    ref = _exact_loop(cfg, W, A["x"], conds, dts, A["text"])
+    assert _rel(got, ref) < 1e-9
+
+
+@pytest.mark.parametrize("name", FP32_TWINS)
+def test_all_warmup_is_the_exact_sampler(name):
+    cfg, W, A, conds, dts = _setup(name)
+    pipe = pp.PipelineOracle(cfg, wl.split_stages(W, 2))
+    got, _ = pipe.run(A["x"], conds, dts, warmup_steps=len(conds), text=A["text"])
+    ref = _exact_loop(cfg, W, A["x"], conds, dts, A["text"])
+    assert _rel(got, ref) < 1e-9
+
+
+def test_pipelined_steps_differ_from_exact_and_converge_with_step_size():
+    """Stale rows are an approximation: the result must differ from the exact sampler (else the buffers are not being
+    used), and the gap must shrink as consecutive steps get more alike (Sec. 3.3: input similarity between steps)."""
+    errs = []
+    for total in (-0.6, -0.2, -0.05):
+        cfg = wl.CONFIGS["K0f"]
+        W = wl.make_weights(cfg, n_layers=2 * cfg["n_layers"])
+        A = wl.make_activations(cfg)
+        conds, dts = wl.make_sampling(cfg, 4, dt_total=total)
+        pipe = pp.PipelineOracle(cfg, wl.split_stages(W, 2))
+        got, _ = pipe.run(A["x"], conds, dts, warmup_steps=1, text=A["text"])
+        errs.append(_rel(got, _exact_loop(cfg, W, A["x"], conds, dts, A["text"])))
+    assert errs[0] > errs[1] > errs[2] > 1e-7
+    assert errs[2] < 0.05
+
+
+@pytest.mark.parametrize("name,N", [("K0f", 3), ("K1f", 2), ("K2f", 3), ("K3f", 2)])
+def test_device_time_order_gives_the_same_values(name, N):
+    """Emulate N devices: at micro-step tau device i runs item k = tau - i, items ordered (step, patch).  Calls are
+    issued micro-step by micro-step (all devices of one micro-step, highest device first, so that nothing is used
+    before the schedule has produced it), with the update applied per patch when the last stage finishes it.
+    Checks (a) the inputs every call needs exist by then when M >= N (no bubbles after start-up), (b) values equal the
+    item-by-item loop of the oracle, (c) busy fraction M*S/(M*S+N-1)."""
+    S = 3
+    cfg = wl.variant(wl.CONFIGS[name], n_layers=1)
+    W = wl.make_weights(cfg, n_layers=N)
+    A = wl.make_activations(cfg)
+    conds, dts = wl.make_sampling(cfg, S + 1)
+    M, n = cfg["n_patches"], wl.patch_rows(cfg)
+    assert M >= N
+    joint = cfg["kind"] in (2, 3)
+    text = A["text"]
+
+    ref_pipe = pp.PipelineOracle(cfg, wl.split_stages(W, N))
+    ref, _ = ref_pipe.run(A["x"], conds, dts, warmup_steps=1, text=text)
+
+    stages = [po.StageOracle(cfg, [W[i]]) for i in range(N)]
+    # warm-up step, synchronous
+    x = np.array(A["x"], np.float64)
+    h, ht = x, text
+    for st in stages:
+        h, ht2 = st.kv_init(h, conds[0], ht)
+        ht = ht2 if joint else text
+    x = x + dts[0] * h
+    # pipelined steps in device-time order
+    xs = {1: x}                                   # xs[s]: latent entering step s (rows filled in patch by patch)
+    for s in range(2, S + 2):
+        xs[s] = np.full_like(x, np.nan)
+    inflight = {}                                 # (item k, stage i) -> (rows, text rows) waiting for device i
+    items = [(s, p) for s in range(1, S + 1) for p in range(M)]
+    busy = 0
+    total_micro = len(items) + N - 1
+    for tau in range(total_micro):
+        for i in reversed(range(N)):
+            k = tau - i
+            if not (0 <= k < len(items)):
+                continue
+            s, p = items[k]
+            if i == 0:
+                rows = xs[s][p * n:(p + 1) * n]
+                assert not np.isnan(rows).any(), "schedule asked for a patch the update has not produced yet"
+                trows = text if (joint and p == 0) else None
+            else:
+                rows, trows = inflight.pop((k, i))
+            if trows is not None:
+                out, tout = stages[i].patch_forward(rows, conds[s], p, text=trows)
+            else:
+                out, tout = stages[i].patch_forward(rows, conds[s], p), None
+            busy += 1
+            if i == N - 1:
+                xs[s + 1][p * n:(p + 1) * n] = xs[s][p * n:(p + 1) * n] + dts[s] * out
+            else:
+                inflight[(k, i + 1)] = (out, tout)
+    assert not inflight
+    assert _rel(xs[S + 1], ref) < 1e-12
+    assert busy / (N * total_micro) == pytest.approx(pp.pipeline_utilisation(M, S, N), rel=1e-12)
+
+
+def test_efficiency_value_printed_in_the_paper():
+    for line in open(os.path.join(HERE, "golden", "pipeline_efficiency.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        M, N, S, pct = line.split()
+        assert round(100.0 * pp.pipeline_utilisation(int(M), int(S), int(N)), 1) == float(pct)
+
+
+def test_euler_update_is_linear():
+    rng = np.random.default_rng(0)
+    x, e = rng.normal(size=(5, 7)), rng.normal(size=(5, 7))
+    assert np.array_equal(pp.euler_update(x, e, 0.0), x)
+    assert np.allclose(pp.euler_update(x, e, -0.25), x - 0.25 * e, rtol=0, atol=0)
+    assert np.allclose(pp.euler_update(pp.euler_update(x, e, 0.1), e, 0.2), pp.euler_update(x, e, 0.3), atol=1e-15)

@@ -198,3 +198,23 @@ def variant(cfg, **kw):
     c = dict(cfg)
     c.update(kw)
     return _cfg(**c)
+
+
+def make_sampling(cfg, steps, dt_total=-0.2, cond_drift=0.1):
+    """Inputs of an S-step sampling loop: per-step conditioning vectors (the timestep embedding drifts from step to
+    step; a fixed part plus a per-step part of relative size cond_drift) and per-step Euler step sizes that sum to
+    dt_total.  Float32, bf16-representable for bf16 workloads."""
+    rng = np.random.Generator(np.random.Philox(key=int(cfg["seed"]) * 1000 + 3))
+    base = make_activations(cfg)["cond"]
+    scale = float(np.sqrt(np.mean(base.astype(np.float64) ** 2)))
+    conds = [_store(cfg, base + np.float32(cond_drift * scale) * _normal(rng, base.shape)) for _ in range(steps)]
+    w = 1.0 + 0.5 * np.cos(np.arange(steps))          # uneven steps, as real noise schedules have
+    dts = [float(dt_total * wi / w.sum()) for wi in w]
+    return conds, dts
+
+
+def split_stages(layers, n_stages):
+    """Consecutive, equal-sized groups of layers (one group per pipeline stage)."""
+    per = len(layers) // n_stages
+    assert per * n_stages == len(layers)
+    return [layers[i * per:(i + 1) * per] for i in range(n_stages)]
