@@ -32,6 +32,18 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// s_waitcnt vmcnt(behind * LPS) for a wave-uniform run-time `behind` in [0, MAXB] (the count is an immediate)
+template <int LPS, int MAXB>
+__device__ __forceinline__ void wait_tiles_behind(int behind) {
+  static_assert(MAXB * LPS <= 63, "vmcnt is a 6-bit counter");
+  if constexpr (MAXB <= 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (behind >= MAXB) wait_vmcnt<MAXB * LPS>();
+    else wait_tiles_behind<LPS, MAXB - 1>(behind);
+  }
+}
+
 __device__ __forceinline__ void lds_load16(const bf16_t *g, unsigned char *lds_wave_uniform) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                    (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
@@ -243,11 +255,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
   }
 
   for (int kt = 0; kt < nk; ++kt) {
-    // tiles still in flight behind tile kt: min(NSTAGE-2, nk-1-kt)
+    // tiles still in flight behind tile kt: min(NSTAGE-2, nk-1-kt); wait until only their loads are outstanding
     const int behind = min(NSTAGE - 2, nk - 1 - kt);
-    if (behind >= 2) wait_vmcnt<2 * LPS>();
-    else if (behind == 1) wait_vmcnt<LPS>();
-    else wait_vmcnt<0>();
+    wait_tiles_behind<LPS, NSTAGE - 2>(behind);
     // plain s_barrier: __syncthreads() would also drain every global load in flight (vmcnt(0)), i.e. the prefetches
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -481,6 +491,8 @@ bool gemm_kv_route_supported(const GemmArgs &a) {
 bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= BK && a.M >= 1 && a.N >= 1; }
 
 int g_gemm_tile_override = 0;   // tuning hook: 0 = heuristic, 1.. = a fixed tile configuration
+int g_wavek_min_k = 2048;       // tuning hook: smallest K the wave-split-K kernel takes
+int g_wavek_max_tiles = 512;    // tuning hook: it takes GEMMs with fewer 64 x 64 tiles than this
 
 // Tile heuristic, from A/B runs inside the stage on MI355X (weights come from HBM there, not from a warm L2, which
 // favours deeper rings than an isolated GEMM loop suggests):
@@ -500,7 +512,7 @@ static int pick_variant(const GemmArgs &a) {
   if (tiles(128, 128) >= 384) return V_128x128;
   if (tiles(128, 64) >= 512) return V_128x64;
   const int64_t t64 = tiles(64, 64);
-  if (t64 < 512 && a.K >= 2048) return V_WAVEK;
+  if (t64 < g_wavek_max_tiles && a.K >= g_wavek_min_k) return V_WAVEK;
   if (t64 <= 512) return V_64x64_S4;
   if (t64 <= 768) return V_64x64_S3;
   return V_64x64_S2;
@@ -535,6 +547,11 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
     case 26: return launch_tile<64, 64, 3>(a, s);
     case 27: return launch_tile<128, 64, 3>(a, s);
+    case 28: return launch_tile<64, 64, 6>(a, s);
+    case 29: return launch_tile<64, 64, 8>(a, s);
+    case 30: return launch_tile<64, 64, 5>(a, s);
+    case 31: return launch_tile<128, 64, 6>(a, s);
+    case 32: return launch_tile<128, 64, 5>(a, s);
     default: break;
   }
   switch (pick_variant(a)) {

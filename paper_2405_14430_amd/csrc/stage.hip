@@ -665,10 +665,12 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 
 }  // extern "C"
 
-namespace pf { extern int g_gemm_tile_override; }
+namespace pf { extern int g_gemm_tile_override, g_wavek_min_k, g_wavek_max_tiles; }
 namespace pf { extern int g_attn_variant; extern int g_attn_stages; }
 extern "C" void pf_tune_gemm_tile(int id) {
-  if (id >= 300) pf::g_attn_stages = id - 300;
+  if (id >= 500) pf::g_wavek_max_tiles = (id - 500) * 16;
+  else if (id >= 400) pf::g_wavek_min_k = (id - 400) * 64;
+  else if (id >= 300) pf::g_attn_stages = id - 300;
   else if (id >= 200) g_fuse_kv_route = id - 200;
   else if (id >= 100) pf::g_attn_variant = id - 100;
   else pf::g_gemm_tile_override = id;
