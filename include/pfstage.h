@@ -84,7 +84,14 @@ typedef struct {
   float rope_theta;    /* kind 3: RoPE base */
   int32_t gelu_tanh;   /* 1: tanh form of GELU, 0: erf form */
   int32_t kernel_path; /* pf_kernel_path */
+  int32_t batch;       /* B: images per call, 0 or 1 = one, at most PF_MAX_BATCH.  B = 2 is one image run with and
+                          without its condition for classifier-free guidance (Sec. 4.1.3 keeps the two on separate device
+                          groups; on one device they share the weights and every GEMM).  Each image has K/V buffers of its
+                          own.  With B > 1 every per-call array gains a leading image axis: x_patch / y_patch [B, n, d],
+                          x_prev / y_prev [B, L, d], cond [B, d or 6d], text / text_out [B, T, ...]. */
 } pf_config;
+
+#define PF_MAX_BATCH 8
 
 /*
  * Weights of one layer (one stream).  Device pointers, dtype elements, [out, in] row-major.
@@ -186,11 +193,14 @@ typedef struct {
   int64_t v_row_stride, v_head_stride, v_col_stride;
 } pf_kv_view_t;
 
-pf_status pf_kv_view(const pf_stage *stage, int layer, pf_kv_view_t *out);
+pf_status pf_kv_view(const pf_stage *stage, int layer, pf_kv_view_t *out);   /* image 0 */
+/* The same for image `image` (0 <= image < B) of a batched stage; cross != 0 selects the cached cross-attention
+ * keys/values (kind 1).  Errors: PF_ERR_NULL, PF_ERR_RANGE, PF_ERR_CONFIG. */
+pf_status pf_kv_view_image(const pf_stage *stage, int layer, int image, int cross, pf_kv_view_t *out);
 /* kind 1: the cached text keys/values of a layer's cross-attention (rows = T). */
 pf_status pf_xattn_kv_view(const pf_stage *stage, int layer, pf_kv_view_t *out);
 
-/* Host-only query: how an attention launch of `nq` query rows over the self (cross = 0) or cross-attention
+/* Host-only query: how an attention launch of `nq` query rows per image over the self (cross = 0) or cross-attention
  * (cross = 1, kind 1) keys would be split over the key range, the bytes of partial results that split writes
  * and the bytes of workspace reserved for them (ws_needed <= ws_reserved always holds). */
 pf_status pf_stage_attention_plan(const pf_stage *stage, int nq, int cross, int *splits, size_t *ws_needed,

@@ -26,7 +26,7 @@ STATUS = {0: "PF_OK", -1: "PF_ERR_NULL", -2: "PF_ERR_CONFIG", -3: "PF_ERR_SHAPE"
 class PfConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("kind", "dtype", "n_layers", "hidden", "n_heads", "head_dim", "mlp_dim",
                                           "seq_img", "n_patches", "text_len", "cross_dim", "grid_h", "grid_w")] + \
-               [("ln_eps", C.c_float), ("rope_theta", C.c_float), ("gelu_tanh", C.c_int32), ("kernel_path", C.c_int32)]
+               [("ln_eps", C.c_float), ("rope_theta", C.c_float), ("gelu_tanh", C.c_int32), ("kernel_path", C.c_int32), ("batch", C.c_int32)]
 
 
 class PfLayerWeights(C.Structure):
@@ -54,7 +54,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention",
-           "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy"]
+           "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image"]
 
 _lib = None
 
@@ -83,6 +83,8 @@ def load_library():
     lib.pf_kv_view.argtypes = [vp, i32, C.POINTER(PfKvView)]
     lib.pf_xattn_kv_view.restype = i32
     lib.pf_xattn_kv_view.argtypes = [vp, i32, C.POINTER(PfKvView)]
+    lib.pf_kv_view_image.restype = i32
+    lib.pf_kv_view_image.argtypes = [vp, i32, i32, i32, C.POINTER(PfKvView)]
     lib.pf_stage_attention_plan.restype = i32
     lib.pf_stage_attention_plan.argtypes = [vp, i32, i32, C.POINTER(C.c_int), C.POINTER(sz), C.POINTER(sz)]
     lib.pf_stage_set_stream.restype = i32
@@ -133,7 +135,7 @@ def make_config(cfg, kernel_path=PF_PATH_AUTO, n_layers=None):
                     seq_img=cfg["seq_img"], n_patches=cfg["n_patches"], text_len=cfg.get("text_len", 0),
                     cross_dim=cfg.get("cross_dim", 0), grid_h=cfg["grid_h"], grid_w=cfg["grid_w"],
                     ln_eps=cfg.get("ln_eps", 1e-6), rope_theta=cfg.get("rope_theta", 1e4),
-                    gelu_tanh=cfg.get("gelu_tanh", 1), kernel_path=kernel_path)
+                    gelu_tanh=cfg.get("gelu_tanh", 1), kernel_path=kernel_path, batch=cfg.get("batch", 1))
 
 
 def torch_dtype(cfg):
@@ -204,7 +206,8 @@ class Stage:
                       text_out=None if text_out is None else text_out.data_ptr())
 
     def kv_init(self, x_prev=None, cond=None, text=None, want_output=False):
-        """x_prev/cond/text: device tensors (x_prev, cond, joint text: float32; kind-1 text: stage dtype)."""
+        """x_prev/cond/text: device tensors (x_prev, cond, joint text: float32; kind-1 text: stage dtype).  A stage with
+        batch B > 1 takes every array with a leading image axis of length B."""
         y = torch.empty_like(x_prev) if (want_output and x_prev is not None) else None
         tout = torch.empty_like(text) if (want_output and self.joint and text is not None and x_prev is not None) else None
         pc = self._cond(cond, text, tout)
@@ -219,9 +222,9 @@ class Stage:
         self._check(self.lib.pf_stage_patch_forward(self.h, _ptr(x_patch), C.byref(pc), int(p), _ptr(y)))
         return (y, text_out) if (self.joint and text is not None) else y
 
-    def _view(self, fn, layer):
+    def _view(self, layer, image, cross):
         v = PfKvView()
-        self._check(fn(self.h, layer, C.byref(v)))
+        self._check(self.lib.pf_kv_view_image(self.h, layer, image, int(cross), C.byref(v)))
         typed = self.kv.view(self.dt)
         H, dh, esz = self.cfg["n_heads"], self.cfg["head_dim"], v.elem_bytes
         ko = (v.k - self.kv.data_ptr()) // esz
@@ -230,12 +233,12 @@ class Stage:
         V = typed.as_strided((v.rows, H, dh), (v.v_row_stride, v.v_head_stride, v.v_col_stride), vo)
         return K, V, v
 
-    def kv_view(self, layer):
+    def kv_view(self, layer, image=0):
         """(K, V) as strided [rows, H, dh] tensor views into the caller-owned buffer, plus the raw view struct."""
-        return self._view(self.lib.pf_kv_view, layer)
+        return self._view(layer, image, False)
 
-    def xattn_kv_view(self, layer):
-        return self._view(self.lib.pf_xattn_kv_view, layer)
+    def xattn_kv_view(self, layer, image=0):
+        return self._view(layer, image, True)
 
     def set_stream(self, stream):
         self._check(self.lib.pf_stage_set_stream(self.h, _stream_ptr(stream)))

@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t *__restrict
                                                         const bf16_t *__restrict__ kbuf,
                                                         const bf16_t *__restrict__ vtbuf, int kv_rows, int Lp, int H,
                                                         int dh, bf16_t *__restrict__ out, int64_t ldo, int nq,
-                                                        int splits, float *__restrict__ ws) {
+                                                        int splits, float *__restrict__ ws, int hpi) {
+  // H counts heads over all images of the call (hpi per image); q / out rows are image-major
   using C = AttnCfg<DH>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t *Ks = reinterpret_cast<bf16_t *>(smem_raw);            // [2][K_ELEMS]
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t *__restrict
   bf16x4 qt = {0, 0, 0, 0};
   {
     const int qi = q0 + l32;
-    const bf16_t *qp = q + (size_t)qi * ldq + (size_t)h * dh;
+    const bf16_t *qp = q + ((size_t)(h / hpi) * nq + qi) * ldq + (size_t)(h % hpi) * dh;
 #pragma unroll
     for (int ks = 0; ks < C::KS16; ++ks) {
       int c = ks * 16 + hi * 8;
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t *__restrict
   const int d = H * dh;
   if (splits == 1) {
     const float inv = 1.f / l_tot;
-    bf16_t *op = out + (size_t)qi * ldo + (size_t)h * dh;
+    bf16_t *op = out + ((size_t)(h / hpi) * nq + qi) * ldo + (size_t)(h % hpi) * dh;
 #pragma unroll
     for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
@@ -261,7 +262,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t *__restrict
 template <int DH>
 hipError_t attn_launch(const AttnArgs &a, hipStream_t s) {
   using C = AttnCfg<DH>;
-  dim3 g((a.nq + TQ - 1) / TQ, a.n_heads, a.splits);
+  const int B = a.batch > 1 ? a.batch : 1;
+  dim3 g((a.nq + TQ - 1) / TQ, a.n_heads * B, a.splits);
   size_t smem = (size_t)(2 * C::K_ELEMS + 2 * C::V_ELEMS) * sizeof(bf16_t);
   static bool attr_done = false;
   if (!attr_done) {
@@ -271,8 +273,8 @@ hipError_t attn_launch(const AttnArgs &a, hipStream_t s) {
     attr_done = true;
   }
   attn_mfma_kernel<DH><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf,
-                                            (const bf16_t *)a.vtbuf, a.kv_rows, a.rows_padded, a.n_heads, a.head_dim,
-                                            (bf16_t *)a.out, a.ldo, a.nq, a.splits, a.ws);
+                                            (const bf16_t *)a.vtbuf, a.kv_rows, a.rows_padded, a.n_heads * B, a.head_dim,
+                                            (bf16_t *)a.out, a.ldo, a.nq, a.splits, a.ws, a.n_heads);
   return hipGetLastError();
 }
 

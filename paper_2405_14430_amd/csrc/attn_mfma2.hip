@@ -65,7 +65,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
                                                             const bf16_t *__restrict__ kbuf,
                                                             const bf16_t *__restrict__ vtbuf, int kv_rows, int Lp, int H,
                                                             bf16_t *__restrict__ out, int64_t ldo, int nq, int splits,
-                                                            int qtiles, float *__restrict__ ws) {
+                                                            int qtiles, float *__restrict__ ws, int hpi) {
+  // H counts heads over all images of the call (image-major, hpi heads per image); q / out rows are image-major too
   using C = Cfg<DH>;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   bf16x4 qtail = {0, 0, 0, 0};
   {
     const int qi = q0 + l32;
-    const bf16_t *qp = q + (size_t)qi * ldq + (size_t)h * DH;
+    const bf16_t *qp = q + ((size_t)(h / hpi) * nq + qi) * ldq + (size_t)(h % hpi) * DH;
 #pragma unroll
     for (int ks = 0; ks < C::KS16; ++ks) {
       uint4 v = make_uint4(0, 0, 0, 0);
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   const int d = H * DH;
   if (splits == 1) {
     const float inv = 1.f / l_tot;
-    bf16_t *op = out + (size_t)qi * ldo + (size_t)h * DH;
+    bf16_t *op = out + ((size_t)(h / hpi) * nq + qi) * ldo + (size_t)(h % hpi) * DH;
 #pragma unroll
     for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
@@ -325,10 +326,11 @@ hipError_t launch2(const AttnArgs &a, hipStream_t s) {
     attr_done = true;
   }
   const int qtiles = (a.nq + TQ - 1) / TQ;
-  dim3 g(qtiles * a.n_heads * a.splits);
+  const int B = a.batch > 1 ? a.batch : 1;
+  dim3 g(qtiles * a.n_heads * B * a.splits);
   attn_mfma2_kernel<DH, NS><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
-                                             a.kv_rows, a.rows_padded, a.n_heads, (bf16_t *)a.out, a.ldo, a.nq, a.splits,
-                                             qtiles, a.ws);
+                                             a.kv_rows, a.rows_padded, a.n_heads * B, (bf16_t *)a.out, a.ldo, a.nq, a.splits,
+                                             qtiles, a.ws, a.n_heads);
   return hipGetLastError();
 }
 

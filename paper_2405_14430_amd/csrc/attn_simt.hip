@@ -12,7 +12,8 @@ template <typename T, int DH>
 __global__ __launch_bounds__(64) void attn_simt_kernel(const T *__restrict__ q, int64_t ldq, const T *__restrict__ kbuf,
                                                        const T *__restrict__ vtbuf, int kv_rows, int Lp, int H, int dh,
                                                        T *__restrict__ out, int64_t ldo, int nq, int splits,
-                                                       float *__restrict__ ws) {
+                                                       float *__restrict__ ws, int hpi) {
+  // H counts heads over all images of the call (hpi per image); q / out rows are image-major
   constexpr int TK = 32;
   __shared__ __attribute__((aligned(16))) float Ks[TK][DH];
   __shared__ __attribute__((aligned(16))) float Vs[DH][TK];
@@ -25,7 +26,7 @@ __global__ __launch_bounds__(64) void attn_simt_kernel(const T *__restrict__ q, 
   float qr[DH], o[DH];
 #pragma unroll
   for (int c = 0; c < DH; ++c) {
-    qr[c] = (active && c < dh) ? to_f32(q[(size_t)i * ldq + (size_t)h * dh + c]) * sm_scale : 0.f;
+    qr[c] = (active && c < dh) ? to_f32(q[((size_t)(h / hpi) * nq + i) * ldq + (size_t)(h % hpi) * dh + c]) * sm_scale : 0.f;
     o[c] = 0.f;
   }
   float m = -INFINITY, l = 0.f;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(64) void attn_simt_kernel(const T *__restrict__ q, 
     float inv = 1.f / l;
 #pragma unroll
     for (int c = 0; c < DH; ++c)
-      if (c < dh) Elem<T>::store(out + (size_t)i * ldo + (size_t)h * dh + c, o[c] * inv);
+      if (c < dh) Elem<T>::store(out + ((size_t)(h / hpi) * nq + i) * ldo + (size_t)(h % hpi) * dh + c, o[c] * inv);
   } else {
     float *op = ws + ((size_t)sp * nq + i) * d + (size_t)h * dh;
 #pragma unroll
@@ -108,11 +109,12 @@ __global__ __launch_bounds__(64) void attn_simt_kernel(const T *__restrict__ q, 
 
 template <typename T>
 static hipError_t attn_simt_dispatch(const AttnArgs &a, hipStream_t s) {
-  dim3 g((a.nq + 63) / 64, a.n_heads, a.splits);
+  const int B = a.batch > 1 ? a.batch : 1;
+  dim3 g((a.nq + 63) / 64, a.n_heads * B, a.splits);
 #define PF_ATTN_SIMT(DH)                                                                                              \
   attn_simt_kernel<T, DH><<<g, 64, 0, s>>>((const T *)a.q, a.ldq, (const T *)a.kbuf, (const T *)a.vtbuf, a.kv_rows,     \
-                                           a.rows_padded, a.n_heads, a.head_dim, (T *)a.out, a.ldo, a.nq, a.splits, \
-                                           a.ws)
+                                           a.rows_padded, a.n_heads * B, a.head_dim, (T *)a.out, a.ldo, a.nq, a.splits, \
+                                           a.ws, a.n_heads)
   if (a.head_dim <= 64) PF_ATTN_SIMT(64);
   else if (a.head_dim <= 72) PF_ATTN_SIMT(72);
   else PF_ATTN_SIMT(128);

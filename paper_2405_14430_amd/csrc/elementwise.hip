@@ -23,10 +23,9 @@ __global__ __launch_bounds__(256) void modulation_kernel(const T *__restrict__ w
 
 // blockIdx.y selects the (layer, stream) entry
 template <typename T>
-__global__ __launch_bounds__(256) void modulation_batch_kernel(ModBatch mb, const float *__restrict__ c, int out_dim,
-                                                               int in_dim, int table_mode) {
+__global__ __launch_bounds__(256) void modulation_batch_kernel(ModBatch mb, int out_dim, int in_dim, int table_mode) {
   const int e = blockIdx.y;
-  modulation_body<T>((const T *)mb.w[e], (const T *)mb.b[e], c, mb.out[e], out_dim, in_dim, table_mode);
+  modulation_body<T>((const T *)mb.w[e], (const T *)mb.b[e], mb.c[e], mb.out[e], out_dim, in_dim, table_mode);
 }
 
 template <typename T>
@@ -60,13 +59,12 @@ __device__ __forceinline__ void modulation_body(const T *__restrict__ w, const T
   }
 }
 
-hipError_t launch_modulation_batch(int dt, const ModBatch &mb, const float *c, int out_dim, int in_dim, int table_mode,
-                                   hipStream_t s) {
+hipError_t launch_modulation_batch(int dt, const ModBatch &mb, int out_dim, int in_dim, int table_mode, hipStream_t s) {
   if (mb.count <= 0) return hipSuccess;
   dim3 g(table_mode ? (out_dim + 255) / 256 : (out_dim + 31) / 32, mb.count);
   size_t sh = table_mode ? 0 : (size_t)in_dim * sizeof(float);
-  if (dt == DT_BF16) modulation_batch_kernel<bf16_t><<<g, 256, sh, s>>>(mb, c, out_dim, in_dim, table_mode);
-  else modulation_batch_kernel<float><<<g, 256, sh, s>>>(mb, c, out_dim, in_dim, table_mode);
+  if (dt == DT_BF16) modulation_batch_kernel<bf16_t><<<g, 256, sh, s>>>(mb, out_dim, in_dim, table_mode);
+  else modulation_batch_kernel<float><<<g, 256, sh, s>>>(mb, out_dim, in_dim, table_mode);
   return hipGetLastError();
 }
 
@@ -98,10 +96,16 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float *__restric
                                                           const float *__restrict__ shift,
                                                           const float *__restrict__ scale, float eps,
                                                           T *__restrict__ out, int64_t ldo, int rows, int d,
-                                                          int normalize) {
+                                                          int normalize, int seg_rows, int64_t seg_stride) {
+  // rows are image-major, seg_rows per image; image b uses shift + b * seg_stride, scale + b * seg_stride
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
+  if (seg_rows > 0) {
+    const int64_t o = (int64_t)(row / seg_rows) * seg_stride;
+    shift += o;
+    scale += o;
+  }
   const float *xr = x + (size_t)row * ldx;
   float4 v[NC];
   float sum = 0.f;
@@ -156,27 +160,29 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float *__restric
 
 template <typename T, int NC>
 static void ln_launch(const float *x, int64_t ldx, const float *shift, const float *scale, float eps, void *out,
-                      int64_t ldo, int rows, int d, int normalize, hipStream_t s) {
+                      int64_t ldo, int rows, int d, int normalize, int seg_rows, int64_t seg_stride, hipStream_t s) {
   ln_modulate_kernel<T, NC><<<dim3((rows + 3) / 4), 256, 0, s>>>(x, ldx, shift, scale, eps, (T *)out, ldo, rows, d,
-                                                                normalize);
+                                                                normalize, seg_rows, seg_stride);
 }
 
 template <typename T>
 static hipError_t ln_dispatch(const float *x, int64_t ldx, const float *shift, const float *scale, float eps,
-                              void *out, int64_t ldo, int rows, int d, int normalize, hipStream_t s) {
+                              void *out, int64_t ldo, int rows, int d, int normalize, int seg_rows, int64_t seg_stride,
+                              hipStream_t s) {
   int need = (d + 255) / 256;
 #define PF_LN_CASE(NC) \
-  if (need <= NC) { ln_launch<T, NC>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, s); return hipGetLastError(); }
+  if (need <= NC) { ln_launch<T, NC>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s); return hipGetLastError(); }
   PF_LN_CASE(2) PF_LN_CASE(4) PF_LN_CASE(5) PF_LN_CASE(6) PF_LN_CASE(8) PF_LN_CASE(12) PF_LN_CASE(16) PF_LN_CASE(32)
 #undef PF_LN_CASE
   return hipErrorInvalidValue;  // d > 8192 is rejected by the caller
 }
 
 hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *shift, const float *scale,
-                              float eps, void *out, int64_t ldo, int rows, int d, int normalize, hipStream_t s) {
+                              float eps, void *out, int64_t ldo, int rows, int d, int normalize, hipStream_t s,
+                              int seg_rows, int64_t seg_stride) {
   if (rows <= 0) return hipSuccess;
-  return dt == DT_BF16 ? ln_dispatch<bf16_t>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, s)
-                       : ln_dispatch<float>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, s);
+  return dt == DT_BF16 ? ln_dispatch<bf16_t>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s)
+                       : ln_dispatch<float>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -290,7 +296,8 @@ size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, T *__restrict__ out,
-                                                           int64_t ldo, int nq, int H, int dh, int splits) {
+                                                           int64_t ldo, int nq, int H, int dh, int splits, int hpi) {
+  // H counts heads over all images of the call (hpi per image); out rows are image-major
   const int d = H * dh;
   const int cpr = d / 4;
   int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -311,19 +318,21 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     o[0] += v.x * wgt; o[1] += v.y * wgt; o[2] += v.z * wgt; o[3] += v.w * wgt;
   }
   float inv = 1.f / L;
-  T *dst = out + (size_t)i * ldo + ch;
+  const int img = h / hpi;
+  T *dst = out + ((size_t)img * nq + i) * ldo + (ch - img * hpi * dh);
 #pragma unroll
   for (int t = 0; t < 4; ++t) Elem<T>::store(dst + t, o[t] * inv);
 }
 
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s) {
-  const int d = a.n_heads * a.head_dim;
+  const int B = a.batch > 1 ? a.batch : 1;
+  const int d = a.n_heads * B * a.head_dim;
   int64_t threads = (int64_t)a.nq * (d / 4);
   dim3 g((unsigned)((threads + 255) / 256));
   if (a.dt == DT_BF16)
-    attn_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads, a.head_dim, a.splits);
+    attn_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
   else
-    attn_combine_kernel<float><<<g, 256, 0, s>>>(a.ws, (float *)a.out, a.ldo, a.nq, a.n_heads, a.head_dim, a.splits);
+    attn_combine_kernel<float><<<g, 256, 0, s>>>(a.ws, (float *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
   return hipGetLastError();
 }
 

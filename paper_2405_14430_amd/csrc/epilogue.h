@@ -16,7 +16,9 @@ struct KvRoute {
   void *kbuf, *vtbuf;          // nullptr kbuf: no routing
   int Lp, dh, d;
   int split, row0a, row0b;
-  const float2 *rope;          // [M][dh/2] (cos, sin) per GEMM row, or nullptr
+  const float2 *rope;          // [rows of one image][dh/2] (cos, sin) per GEMM row, or nullptr
+  int seg;                     // > 0: GEMM rows are image-major, seg rows per image; mapping applies inside the image
+  int64_t img_stride;          // elements between consecutive images' K (and V^T) buffers
 };
 
 template <typename T>
@@ -26,8 +28,13 @@ struct Epilogue {
   void *C; int64_t ldc;
   int mode, gelu_from, gelu_tanh;
   const float *gate;
+  int gate_seg; int64_t gate_stride;   // gate_seg > 0: row r reads gate + (r / gate_seg) * gate_stride
   const float *R; int64_t ldr;
   T *C2; int64_t ldc2;
+
+  __device__ __forceinline__ const float *gate_of(int row) const {
+    return gate_seg > 0 ? gate + (int64_t)(row / gate_seg) * gate_stride : gate;
+  }
 
   __device__ __forceinline__ void apply(int row, int col, float acc) const {
     float v = acc + (bias ? to_f32(bias[col]) : 0.f);
@@ -35,7 +42,7 @@ struct Epilogue {
       if (col >= gelu_from) v = gelu_f(v, gelu_tanh);
       Elem<T>::store(reinterpret_cast<T *>(C) + (size_t)row * ldc + col, v);
     } else {
-      float g = gate ? gate[col] : 1.f;
+      float g = gate ? gate_of(row)[col] : 1.f;
       float x = R[(size_t)row * ldr + col] + g * v;
       reinterpret_cast<float *>(C)[(size_t)row * ldc + col] = x;
       if (C2) Elem<T>::store(C2 + (size_t)row * ldc2 + col, x);
@@ -47,9 +54,9 @@ template <typename T, typename Args>
 inline Epilogue<T> make_epilogue(const Args &a) {
   Epilogue<T> e;
   e.kv = KvRoute{a.kvr.kbuf, a.kvr.vtbuf, a.kvr.Lp, a.kvr.dh, a.kvr.d, a.kvr.split, a.kvr.row0a, a.kvr.row0b,
-                 (const float2 *)a.kvr.rope};
+                 (const float2 *)a.kvr.rope, a.kvr.seg, a.kvr.img_stride};
   e.bias = (const T *)a.bias; e.C = a.C; e.ldc = a.ldc; e.mode = a.epilogue; e.gelu_from = a.gelu_from;
-  e.gelu_tanh = a.gelu_tanh; e.gate = a.gate; e.R = a.R; e.ldr = a.ldr; e.C2 = (T *)a.C2; e.ldc2 = a.ldc2;
+  e.gelu_tanh = a.gelu_tanh; e.gate = a.gate; e.gate_seg = a.gate_seg; e.gate_stride = a.gate_stride; e.R = a.R; e.ldr = a.ldr; e.C2 = (T *)a.C2; e.ldc2 = a.ldc2;
   return e;
 }
 

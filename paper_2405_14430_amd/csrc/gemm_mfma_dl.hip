@@ -89,8 +89,10 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
       const KvRoute &kv = epi.kv;
       const int part = col / kv.d, cc = col - part * kv.d;
       const int hh = cc / kv.dh, ch = cc - hh * kv.dh;
+      const int img = kv.seg > 0 ? row / kv.seg : 0;
+      const int lrow = row - img * kv.seg;           // row inside its image
       if (kv.rope && part < 2) {
-        const float2 *tab = kv.rope + (size_t)row * (kv.dh >> 1) + (ch >> 1);
+        const float2 *tab = kv.rope + (size_t)lrow * (kv.dh >> 1) + (ch >> 1);
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
           float2 cs = tab[e >> 1];
@@ -105,8 +107,9 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
       if (part == 0) {
         *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(epi.C) + (size_t)row * epi.ldc + col) = o;
       } else if (part == 1) {
-        const int brow = row < kv.split ? kv.row0a + row : kv.row0b + (row - kv.split);
-        *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(kv.kbuf) + ((size_t)hh * kv.Lp + brow) * kv.dh + ch) = o;
+        const int brow = lrow < kv.split ? kv.row0a + lrow : kv.row0b + (lrow - kv.split);
+        *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(kv.kbuf) + (size_t)img * kv.img_stride +
+                                    ((size_t)hh * kv.Lp + brow) * kv.dh + ch) = o;
       }
       // part 2 (v) is written by the transposed pass below
     } else if (epi.mode == 0) {
@@ -124,7 +127,8 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
       float4 r0 = *reinterpret_cast<const float4 *>(rp), r1 = *reinterpret_cast<const float4 *>(rp + 4);
       float x[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
       if (epi.gate) {
-        float4 g0 = *reinterpret_cast<const float4 *>(epi.gate + col), g1 = *reinterpret_cast<const float4 *>(epi.gate + col + 4);
+        const float *gp = epi.gate_of(row) + col;
+        float4 g0 = *reinterpret_cast<const float4 *>(gp), g1 = *reinterpret_cast<const float4 *>(gp + 4);
         float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] += gg[e] * v[e];
@@ -157,16 +161,21 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
       bf16x8 o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(tile[(rg * 8 + e) * TLD + cl] + b);
-      bf16_t *vt = reinterpret_cast<bf16_t *>(kv.vtbuf) + (size_t)cc * kv.Lp;   // cc = h*dh + c
-      const int brow = row < kv.split ? kv.row0a + row : kv.row0b + (row - kv.split);
-      const bool whole = row + 8 <= M && (row >= kv.split || row + 8 <= kv.split);
+      bf16_t *vt = reinterpret_cast<bf16_t *>(kv.vtbuf) + (size_t)cc * kv.Lp;   // cc = h*dh + c; image 0
+      const int img = kv.seg > 0 ? row / kv.seg : 0;
+      const int lrow = row - img * kv.seg;
+      const int brow = lrow < kv.split ? kv.row0a + lrow : kv.row0b + (lrow - kv.split);
+      const bool whole = row + 8 <= M && (kv.seg <= 0 || lrow + 8 <= kv.seg) && (lrow >= kv.split || lrow + 8 <= kv.split);
       if (whole && (brow & 7) == 0) {
-        *reinterpret_cast<bf16x8 *>(vt + brow) = o;
+        *reinterpret_cast<bf16x8 *>(vt + (size_t)img * kv.img_stride + brow) = o;
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int r2 = row + e;
-          if (r2 < M) vt[r2 < kv.split ? kv.row0a + r2 : kv.row0b + (r2 - kv.split)] = o[e];
+          if (r2 >= M) break;
+          const int i2 = kv.seg > 0 ? r2 / kv.seg : 0;
+          const int l2 = r2 - i2 * kv.seg;
+          vt[(size_t)i2 * kv.img_stride + (l2 < kv.split ? kv.row0a + l2 : kv.row0b + (l2 - kv.split))] = o[e];
         }
       }
     }
@@ -439,7 +448,7 @@ bool vec_epilogue_ok(const GemmArgs &a) {
   auto al = [](const void *p, uintptr_t n) { return ((uintptr_t)p % n) == 0; };
   bool ok = (!a.bias || al(a.bias, 16));
   if (a.epilogue == 0) return ok && al(a.C, 16) && a.ldc % 8 == 0;
-  ok = ok && al(a.C, 16) && a.ldc % 4 == 0 && al(a.R, 16) && a.ldr % 4 == 0 && (!a.gate || al(a.gate, 16));
+  ok = ok && al(a.C, 16) && a.ldc % 4 == 0 && al(a.R, 16) && a.ldr % 4 == 0 && (!a.gate || (al(a.gate, 16) && a.gate_stride % 4 == 0));
   if (a.C2) ok = ok && al(a.C2, 16) && a.ldc2 % 8 == 0;
   return ok;
 }

@@ -16,23 +16,27 @@ inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
 hipError_t launch_modulation(int dt, const void *w, const void *b, const float *c, float *mod, int out_dim,
                              int in_dim, int table_mode, hipStream_t s);
 
-// Up to kMax modulation vectors (layers x streams) in one launch; all share cond and the shapes.
+// Up to kMax modulation vectors (layers x streams x images) in one launch; all share the shapes.
 struct ModBatch {
   static constexpr int kMax = 16;
   const void *w[kMax];
   const void *b[kMax];
+  const float *c[kMax];   // conditioning vector of the entry (differs per image of a batch)
   float *out[kMax];
   int count;
 };
-hipError_t launch_modulation_batch(int dt, const ModBatch &mb, const float *c, int out_dim, int in_dim, int table_mode,
-                                   hipStream_t s);
+hipError_t launch_modulation_batch(int dt, const ModBatch &mb, int out_dim, int in_dim, int table_mode, hipStream_t s);
 
+// seg_rows > 0: rows are image-major with seg_rows rows per image and image b reads its shift / scale vectors
+// seg_stride floats after image 0's.
 hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *shift, const float *scale,
                               float eps, void *out, int64_t ldo, int rows, int d, int normalize,
-                              hipStream_t s);
+                              hipStream_t s, int seg_rows = 0, int64_t seg_stride = 0);
 
 struct KvRoute;   // epilogue.h
-struct GemmArgsKv { void *kbuf, *vtbuf; int Lp, dh, d, split, row0a, row0b; const void *rope; };
+// seg > 0: GEMM rows are image-major, seg per image; image b writes into kbuf / vtbuf + b * img_stride elements and
+// the row mapping (split, row0a, row0b, rope row) applies to the row index inside the image.
+struct GemmArgsKv { void *kbuf, *vtbuf; int Lp, dh, d, split, row0a, row0b; const void *rope; int seg; int64_t img_stride; };
 
 struct GemmArgs {
   int dt, path;
@@ -44,6 +48,7 @@ struct GemmArgs {
   int epilogue;        // 0: store dtype (+GELU from column gelu_from); 1: fp32 residual update
   int gelu_from, gelu_tanh;
   const float *gate;   // [N] or nullptr
+  int gate_seg; int64_t gate_stride;   // gate_seg > 0: row r uses gate + (r / gate_seg) * gate_stride (image-major rows)
   const float *R; int64_t ldr;
   void *C2; int64_t ldc2;
   GemmArgsKv kvr;      // kbuf == nullptr: plain GEMM
@@ -72,6 +77,8 @@ struct AttnArgs {
   void *out; int64_t ldo;
   int nq, splits;
   float *ws;           // partial results when splits > 1
+  int batch;           // images per call (0 or 1: one).  q / out hold batch x nq rows, image-major; kbuf / vtbuf hold
+                       // batch x n_heads heads, image-major; the workspace is sized for n_heads * batch heads
 };
 size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits);
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s, bool *used_combine);

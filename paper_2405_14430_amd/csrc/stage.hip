@@ -25,6 +25,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Derived {
   int n, T, Tj, Lkv, Lp, Tp, Rmax, mod_chunks, n_streams;
+  int B;          // images per call (classifier-free guidance runs the conditional and unconditional image together)
   size_t esz;
 };
 
@@ -49,6 +50,7 @@ const char *check_config(const pf_config *c, pf_status *st) {
     if (c->cross_dim < 8 || c->cross_dim % 8) return "cross_dim must be a positive multiple of 8";
   }
   if (c->kind == PF_BLOCK_ADALN_ZERO && c->text_len != 0) return "kind 0 has no text";
+  if (c->batch < 0 || c->batch > PF_MAX_BATCH) return "batch must be in [0, PF_MAX_BATCH] (0 means 1)";
   if (!(c->ln_eps > 0.f)) return "ln_eps must be > 0";
   if (c->kind == PF_BLOCK_SINGLE_STREAM && !(c->rope_theta > 1.f)) return "rope_theta must be > 1";
   *st = PF_OK;
@@ -67,6 +69,7 @@ Derived derive(const pf_config *c) {
   d.mod_chunks = c->kind == PF_BLOCK_SINGLE_STREAM ? 3 : 6;
   d.n_streams = c->kind == PF_BLOCK_MMDIT_JOINT ? 2 : 1;
   d.esz = dt_size(c->dtype);
+  d.B = c->batch > 1 ? c->batch : 1;
   return d;
 }
 
@@ -101,7 +104,7 @@ int choose_splits(int path, int nq, int H, int kv_rows) {
 size_t kv_layer_bytes(const pf_config *c, const Derived &d) {
   size_t self = 2 * (size_t)c->n_heads * d.Lp * c->head_dim * d.esz;
   size_t cross = c->kind == PF_BLOCK_ADALN_SINGLE_XATTN ? 2 * (size_t)c->n_heads * d.Tp * c->head_dim * d.esz : 0;
-  return self + cross;
+  return (self + cross) * d.B;
 }
 
 struct WsLayout {
@@ -114,8 +117,8 @@ WsLayout ws_layout(const pf_config *c, const Derived &d) {
   WsLayout w{};
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  const size_t R = d.Rmax, D = c->hidden, F = c->mlp_dim, e = d.esz;
-  w.mod = take((size_t)d.n_streams * c->n_layers * d.mod_chunks * D * sizeof(float));
+  const size_t R = (size_t)d.Rmax * d.B, D = c->hidden, F = c->mlp_dim, e = d.esz;
+  w.mod = take((size_t)d.B * d.n_streams * c->n_layers * d.mod_chunks * D * sizeof(float));
   w.xres = take(R * D * sizeof(float));
   w.h = take(R * D * e);
   w.qkv = take(R * 3 * D * e);
@@ -132,16 +135,18 @@ WsLayout ws_layout(const pf_config *c, const Derived &d) {
     w.xb = take(R * D * e);
     w.qc = take(R * D * e);
   }
-  if (c->kind == PF_BLOCK_SINGLE_STREAM) w.rope = take(R * (size_t)(c->head_dim / 2) * 2 * sizeof(float));
+  if (c->kind == PF_BLOCK_SINGLE_STREAM) w.rope = take((size_t)d.Rmax * (size_t)(c->head_dim / 2) * 2 * sizeof(float));
   const int path = use_path(c);
   size_t ab = 0;
   // every query-row count a call can have: image-only patch, patch with the joint text rows, warm-up pass
-  int shapes[3] = {d.n, d.n + d.Tj, d.Lkv};
+  // (per image; with a batch the text rows of the MMDiT kind are a launch of their own)
+  int shapes[5] = {d.n, d.n + d.Tj, d.Lkv, d.Tj > 0 ? d.Tj : d.n, c->seq_img};
+  const int HB = c->n_heads * d.B;
   for (int nq : shapes) {
-    size_t b = attention_ws_bytes(nq, c->n_heads, c->head_dim, choose_splits(path, nq, c->n_heads, d.Lkv));
+    size_t b = attention_ws_bytes(nq, HB, c->head_dim, choose_splits(path, nq, HB, d.Lkv));
     if (b > ab) ab = b;
     if (c->kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
-      b = attention_ws_bytes(nq, c->n_heads, c->head_dim, choose_splits(path, nq, c->n_heads, d.T));
+      b = attention_ws_bytes(nq, HB, c->head_dim, choose_splits(path, nq, HB, d.T));
       if (b > ab) ab = b;
     }
   }
@@ -169,12 +174,18 @@ struct pf_stage {
   std::vector<Ev> events;
   std::vector<hipEvent_t> pool;
 
+  // Layer l of the caller's K/V buffer: [K of image 0 .. B-1][V^T of image 0 .. B-1][cross K ...][cross V^T ...], each
+  // image's part head-major.  img_elems / ximg_elems: elements between consecutive images.
+  size_t img_elems() const { return (size_t)cfg.n_heads * d.Lp * cfg.head_dim; }
+  size_t ximg_elems() const { return (size_t)cfg.n_heads * d.Tp * cfg.head_dim; }
   char *kptr(int l) const { return kv + (size_t)l * kv_layer_bytes(&cfg, d); }
-  char *vptr(int l) const { return kptr(l) + (size_t)cfg.n_heads * d.Lp * cfg.head_dim * d.esz; }
-  char *kcptr(int l) const { return kptr(l) + 2 * (size_t)cfg.n_heads * d.Lp * cfg.head_dim * d.esz; }
-  char *vcptr(int l) const { return kcptr(l) + (size_t)cfg.n_heads * d.Tp * cfg.head_dim * d.esz; }
-  float *mod(int stream_idx, int l) const {
-    return (float *)(ws + w.mod) + ((size_t)stream_idx * cfg.n_layers + l) * d.mod_chunks * cfg.hidden;
+  char *vptr(int l) const { return kptr(l) + d.B * img_elems() * d.esz; }
+  char *kcptr(int l) const { return kptr(l) + 2 * d.B * img_elems() * d.esz; }
+  char *vcptr(int l) const { return kcptr(l) + d.B * ximg_elems() * d.esz; }
+  // modulation vectors: [image][stream][layer][chunks * hidden]
+  size_t mod_img_stride() const { return (size_t)d.n_streams * cfg.n_layers * d.mod_chunks * cfg.hidden; }
+  float *mod(int stream_idx, int l, int b = 0) const {
+    return (float *)(ws + w.mod) + b * mod_img_stride() + ((size_t)stream_idx * cfg.n_layers + l) * d.mod_chunks * cfg.hidden;
   }
 };
 
@@ -213,9 +224,10 @@ hipError_t run(pf_stage *s, int cls, Fn &&fn) {
 
 hipError_t gemm(pf_stage *s, int cls, const void *A, int64_t lda, const void *W, int64_t ldw, const void *bias,
                 void *C, int64_t ldc, int M, int N, int K, int epilogue, int gelu_from, const float *gate,
-                const float *R, int64_t ldr, void *C2, int64_t ldc2, const GemmArgsKv *kvr = nullptr) {
+                const float *R, int64_t ldr, void *C2, int64_t ldc2, const GemmArgsKv *kvr = nullptr, int gate_seg = 0) {
   GemmArgs g{};
   if (kvr) g.kvr = *kvr;
+  if (gate && gate_seg > 0 && s->d.B > 1) { g.gate_seg = gate_seg; g.gate_stride = (int64_t)s->mod_img_stride(); }
   g.dt = s->cfg.dtype; g.path = use_path(&s->cfg);
   g.A = A; g.lda = lda; g.W = W; g.ldw = ldw; g.bias = bias; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.epilogue = epilogue; g.gelu_from = gelu_from; g.gelu_tanh = s->cfg.gelu_tanh; g.gate = gate; g.R = R; g.ldr = ldr;
@@ -223,12 +235,14 @@ hipError_t gemm(pf_stage *s, int cls, const void *A, int64_t lda, const void *W,
   return run(s, cls, [&] { return launch_gemm(g, s->stream); });
 }
 
+// (nq = query rows per image; every launch covers all images of the call)
 // Split count of an attention launch of this stage: the occupancy heuristic, lowered if needed so that the partial
 // results never exceed the workspace region reserved for them.
 int plan_splits(const pf_stage *s, int nq, int kv_rows) {
   const int path = use_path(&s->cfg);
-  int splits = choose_splits(path, nq, s->cfg.n_heads, kv_rows);
-  while (splits > 1 && attention_ws_bytes(nq, s->cfg.n_heads, s->cfg.head_dim, splits) > s->w.attn_bytes) --splits;
+  const int HB = s->cfg.n_heads * s->d.B;
+  int splits = choose_splits(path, nq, HB, kv_rows);
+  while (splits > 1 && attention_ws_bytes(nq, HB, s->cfg.head_dim, splits) > s->w.attn_bytes) --splits;
   return splits;
 }
 
@@ -238,6 +252,7 @@ hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const voi
   a.dt = s->cfg.dtype; a.path = use_path(&s->cfg);
   a.q = q; a.ldq = ldq; a.kbuf = kb; a.vtbuf = vb; a.kv_rows = kv_rows; a.rows_padded = rows_padded;
   a.n_heads = s->cfg.n_heads; a.head_dim = s->cfg.head_dim; a.out = out; a.ldo = ldo; a.nq = nq;
+  a.batch = s->d.B;
   a.splits = plan_splits(s, nq, kv_rows);
   a.ws = (float *)(s->ws + s->w.attn);
   hipError_t e = run(s, cls, [&] { return a.path == PATH_SIMT ? launch_attn_simt(a, s->stream) : launch_attn_bf16(a, s->stream); });
@@ -246,17 +261,20 @@ hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const voi
   return e;
 }
 
-// QKV projection of `rows` rows plus the write of their K/V into the layer's buffers (buffer row of GEMM row r:
-// r < split ? row0a + r : row0b + r - split).  When the bf16 GEMM's vectorised epilogue can do it, k and v go straight
-// from the accumulators into K / V^T (q, and RoPE through `rope_tab`, likewise); otherwise the projection lands in the
-// qkv workspace and the scatter kernel moves (and rotates) it.
-pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, char *qs, int rows, char *kb, char *vb,
+// QKV projection of `rows` rows plus the write of their K/V into the layer's buffers.  Rows are image-major, `seg` per
+// image (rows = B * seg); inside an image, row r goes to buffer row (r < split ? row0a + r : row0b + r - split).  When
+// the bf16 GEMM's vectorised epilogue can do it, k and v go straight from the accumulators into K / V^T (q, and RoPE
+// through `rope_tab`, likewise); otherwise the projection lands in the qkv workspace and the scatter kernel moves (and
+// rotates) it, one launch per image and row range.
+pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, char *qs, int seg, char *kb, char *vb,
                       int split, int row0a, int row0b, const void *rope_tab, int tok0) {
   const pf_config &c = s->cfg;
   const Derived &d = s->d;
   const int D = c.hidden;
+  const int rows = seg * d.B;
   const bool rope = c.kind == PF_BLOCK_SINGLE_STREAM;
-  GemmArgsKv kvr{kb, vb, d.Lp, c.head_dim, D, split, row0a, row0b, rope ? rope_tab : nullptr};
+  GemmArgsKv kvr{kb, vb, d.Lp, c.head_dim, D, split, row0a, row0b, rope ? rope_tab : nullptr, d.B > 1 ? seg : 0,
+                 (int64_t)s->img_elems()};
   GemmArgs probe{};
   probe.dt = c.dtype; probe.path = use_path(&c); probe.A = hs; probe.lda = D; probe.W = lw.w_qkv; probe.ldw = D;
   probe.bias = lw.b_qkv; probe.C = qs; probe.ldc = 3 * D; probe.M = rows; probe.N = 3 * D; probe.K = D; probe.epilogue = 0;
@@ -269,130 +287,164 @@ pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, c
   PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, lw.w_qkv, D, lw.b_qkv, qs, 3 * D, rows, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0,
               nullptr, 0));
   hipStream_t st = s->stream;
-  if (split > 0) {
-    ScatterArgs sa{c.dtype, qs, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, row0a, split, rope ? 1 : 0, -1, c.grid_w, c.rope_theta};
-    PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+  for (int b = 0; b < d.B; ++b) {
+    char *qb = qs + (size_t)b * seg * 3 * D * d.esz;
+    char *kbb = kb + (size_t)b * s->img_elems() * d.esz, *vbb = vb + (size_t)b * s->img_elems() * d.esz;
+    if (split > 0) {
+      ScatterArgs sa{c.dtype, qb, 3 * D, kbb, vbb, d.Lp, c.n_heads, c.head_dim, row0a, split, rope ? 1 : 0, -1, c.grid_w, c.rope_theta};
+      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
+    }
+    ScatterArgs sb{c.dtype, qb + (size_t)split * 3 * D * d.esz, 3 * D, kbb, vbb, d.Lp, c.n_heads, c.head_dim, row0b, seg - split,
+                   rope ? 1 : 0, tok0, c.grid_w, c.rope_theta};
+    PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sb, st); }));
   }
-  ScatterArgs sb{c.dtype, qs + (size_t)split * 3 * D * d.esz, 3 * D, kb, vb, d.Lp, c.n_heads, c.head_dim, row0b, rows - split,
-                 rope ? 1 : 0, tok0, c.grid_w, c.rope_theta};
-  PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sb, st); }));
   return PF_OK;
 }
 
-// The block stack on image rows [img_off, img_off + n_img) and, for the joint kinds, on the T text rows when
-// `text` is given.  Residual rows live in the workspace, text rows first.
+// Device-to-device copy of B blocks of `block` floats each, source blocks src_pitch floats apart, destination blocks
+// dst_pitch floats apart (one plain copy when both are dense or B = 1).
+hipError_t copy_blocks(float *dst, size_t dst_pitch, const float *src, size_t src_pitch, size_t block, int B, hipStream_t st) {
+  if (B == 1 || (dst_pitch == block && src_pitch == block))
+    return hipMemcpyAsync(dst, src, (size_t)B * block * sizeof(float), hipMemcpyDeviceToDevice, st);
+  return hipMemcpy2DAsync(dst, dst_pitch * sizeof(float), src, src_pitch * sizeof(float), block * sizeof(float), B,
+                          hipMemcpyDeviceToDevice, st);
+}
+
+// The block stack on image rows [img_off, img_off + n_img) of each of the B images of the call and, for the joint kinds,
+// on the T text rows of each image when `text` is given.  x_img / y_img: [B][n_img][D]; cond: [B][D or 6D]; text /
+// text_out: [B][T][D].  Residual rows live in the workspace when text rows ride along: per image [text; image] for the
+// single-stream kind (one weight set for both), all text rows then all image rows for the MMDiT kind (one weight set
+// per stream, so each stream is one contiguous GEMM operand).
 pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const float *cond, const float *text,
                   float *y_img, float *text_out) {
   const pf_config &c = s->cfg;
   const Derived &d = s->d;
   const WsLayout &w = s->w;
-  const int D = c.hidden, F = c.mlp_dim, dt = c.dtype;
+  const int D = c.hidden, F = c.mlp_dim, dt = c.dtype, B = d.B;
   const size_t e = d.esz;
-  const int Tt = (text && d.Tj) ? d.Tj : 0;   // text rows processed by this call
-  const int R = Tt + n_img;
+  const int Tt = (text && d.Tj) ? d.Tj : 0;   // text rows per image processed by this call
+  const int R = Tt + n_img;                   // rows per image
+  const bool single = c.kind == PF_BLOCK_SINGLE_STREAM;
+  const size_t mstride = s->mod_img_stride();
   hipStream_t st = s->stream;
   char *ws = s->ws;
   float *xres = (float *)(ws + w.xres);
   char *h = ws + w.h, *qkv = ws + w.qkv, *a = ws + w.a, *u = ws + w.u;
 
-  // Residual rows.  With text rows riding along they are gathered in the workspace, text first.  Without, nothing is
-  // copied: the first layer reads x_img directly, the first residual GEMM writes into the output buffer (or the
-  // workspace when the caller wants no output) and everything after that runs in place there.
+  // Residual rows.  With text rows riding along they are gathered in the workspace.  Without, nothing is copied: the
+  // first layer reads x_img directly, the first residual GEMM writes into the output buffer (or the workspace when
+  // the caller wants no output) and everything after that runs in place there.
   float *xbuf = xres;          // where updated residual rows live
   const float *xsrc = xres;    // where the current residual rows are read from (x_img until the first update)
+  // text block / image block of the residual rows: first row and distance between images, in rows
+  const size_t t_row0 = 0, i_row0 = single ? (size_t)Tt : (size_t)B * Tt;
+  const size_t t_pitch = single ? (size_t)R : (size_t)Tt, i_pitch = single ? (size_t)R : (size_t)n_img;
   if (Tt) {
-    PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres, text, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
-    PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(xres + (size_t)Tt * D, x_img, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+    PF_TRY(run(s, PF_KC_COPY, [&] { return copy_blocks(xres + t_row0 * D, t_pitch * D, text, (size_t)Tt * D, (size_t)Tt * D, B, st); }));
+    PF_TRY(run(s, PF_KC_COPY, [&] { return copy_blocks(xres + i_row0 * D, i_pitch * D, x_img, (size_t)n_img * D, (size_t)n_img * D, B, st); }));
   } else {
     xsrc = x_img;
     if (y_img) xbuf = y_img;
   }
 
-  // a0: modulation vectors of every layer (and stream), one launch per 16 of them
+  // a0: modulation vectors of every layer, stream and image, one launch per 16 of them
   {
     ModBatch mb{};
     const int out_dim = d.mod_chunks * D;
     const int table = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
+    const size_t cdim = table ? (size_t)6 * D : (size_t)D;
     auto flush = [&]() -> hipError_t {
       if (mb.count == 0) return hipSuccess;
-      hipError_t e2 = run(s, PF_KC_MODULATION, [&] { return launch_modulation_batch(dt, mb, cond, out_dim, D, table, st); });
+      hipError_t e2 = run(s, PF_KC_MODULATION, [&] { return launch_modulation_batch(dt, mb, out_dim, D, table, st); });
       mb.count = 0;
       return e2;
     };
-    for (int l = 0; l < c.n_layers; ++l) {
-      for (int si = 0; si < d.n_streams; ++si) {
-        if (c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt) continue;   // text stream idle
-        const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
-        mb.w[mb.count] = lw.w_mod; mb.b[mb.count] = lw.b_mod; mb.out[mb.count] = s->mod(si, l);
-        if (++mb.count == ModBatch::kMax) PF_TRY(flush());
-      }
-    }
+    for (int b = 0; b < B; ++b)
+      for (int l = 0; l < c.n_layers; ++l)
+        for (int si = 0; si < d.n_streams; ++si) {
+          if (c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt) continue;   // text stream idle
+          const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
+          mb.w[mb.count] = lw.w_mod; mb.b[mb.count] = lw.b_mod; mb.c[mb.count] = cond + b * cdim;
+          mb.out[mb.count] = s->mod(si, l, b);
+          if (++mb.count == ModBatch::kMax) PF_TRY(flush());
+        }
     PF_TRY(flush());
   }
 
   const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
-  if (c.kind == PF_BLOCK_SINGLE_STREAM)    // (cos, sin) of every row's RoPE angles, shared by all layers of the call
+  if (single)    // (cos, sin) of the RoPE angles of one image's rows, shared by all layers and images of the call
     PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_rope_table(ws + w.rope, R, Tt, img_off, c.grid_w, c.head_dim, c.rope_theta, st); }));
   for (int l = 0; l < c.n_layers; ++l) {
     char *kb = s->kptr(l), *vb = s->vptr(l);
-    if (c.kind == PF_BLOCK_SINGLE_STREAM) {
+    if (single) {
       const pf_layer_weights &lw = s->img[l];
       const float *m = s->mod(0, l);
-      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xsrc, D, m, m + D, c.ln_eps, h, D, R, D, 1, st); }));
+      const int RT = B * R;
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xsrc, D, m, m + D, c.ln_eps, h, D, RT, D, 1, st, B > 1 ? R : 0, mstride); }));
       {
         pf_status qs_ = qkv_project(s, h, lw, qkv, R, kb, vb, Tt, 0, row0_img, ws + w.rope, img_off);
         if (qs_ != PF_OK) return qs_;
       }
       // MLP branch runs in parallel with attention: GELU(h W_up^T + b) lands right of the attention columns
-      PF_TRY(gemm(s, PF_KC_GEMM_UP, h, D, lw.w_up, D, lw.b_up, a + (size_t)D * e, D + F, R, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
+      PF_TRY(gemm(s, PF_KC_GEMM_UP, h, D, lw.w_up, D, lw.b_up, a + (size_t)D * e, D + F, RT, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
       PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D + F, R));
-      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xbuf, D, R, D, D + F, 1, 0, m + 2 * D, xsrc, D, nullptr, 0));
+      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xbuf, D, RT, D, D + F, 1, 0, m + 2 * D, xsrc, D, nullptr, 0, nullptr, R));
       xsrc = xbuf;
       continue;
     }
 
-    // kinds 0, 1, 2: streams = [text (kind 2, if present), image]
-    struct Stream { const pf_layer_weights *lw; const float *m; int r0, nr, brow0; };
+    // kinds 0, 1, 2: streams = [text (kind 2, if present), image]; r0 = first residual row, seg = rows per image
+    struct Stream { const pf_layer_weights *lw; const float *m; size_t r0; int seg, brow0; };
     Stream streams[2];
     int ns = 0;
-    if (c.kind == PF_BLOCK_MMDIT_JOINT && Tt) streams[ns++] = Stream{&s->txt[l], s->mod(0, l), 0, Tt, 0};
-    streams[ns++] = Stream{&s->img[l], s->mod(d.n_streams - 1, l), Tt, n_img, row0_img};
+    if (c.kind == PF_BLOCK_MMDIT_JOINT && Tt) streams[ns++] = Stream{&s->txt[l], s->mod(0, l), t_row0, Tt, 0};
+    streams[ns++] = Stream{&s->img[l], s->mod(d.n_streams - 1, l), Tt ? i_row0 : 0, n_img, row0_img};
 
     for (int si = 0; si < ns; ++si) {
       const Stream &sm = streams[si];
-      const float *xs = xsrc + (size_t)sm.r0 * D;
-      char *hs = h + (size_t)sm.r0 * D * e;
-      char *qs = qkv + (size_t)sm.r0 * 3 * D * e;
-      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, sm.nr, D, 1, st); }));
-      pf_status qs_ = qkv_project(s, hs, *sm.lw, qs, sm.nr, kb, vb, 0, 0, sm.brow0, nullptr, -1);
+      const float *xs = xsrc + sm.r0 * D;
+      char *hs = h + sm.r0 * D * e;
+      char *qs = qkv + sm.r0 * 3 * D * e;
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, B * sm.seg, D, 1, st, B > 1 ? sm.seg : 0, mstride); }));
+      pf_status qs_ = qkv_project(s, hs, *sm.lw, qs, sm.seg, kb, vb, 0, 0, sm.brow0, nullptr, -1);
       if (qs_ != PF_OK) return qs_;
     }
-    PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R));
+    if (B == 1) {
+      // one image: the text and image rows are adjacent, one launch covers both
+      PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R));
+    } else {
+      for (int si = 0; si < ns; ++si)
+        PF_TRY(attention(s, PF_KC_ATTENTION, qkv + streams[si].r0 * 3 * D * e, 3 * D, kb, vb, d.Lkv, d.Lp,
+                         a + streams[si].r0 * D * e, D, streams[si].seg));
+    }
     for (int si = 0; si < ns; ++si) {
       const Stream &sm = streams[si];
-      float *xs = xbuf + (size_t)sm.r0 * D;
-      const float *xs_in = xsrc + (size_t)sm.r0 * D;   // differs from xs only before the first update
-      char *hs = h + (size_t)sm.r0 * D * e;
-      char *as = a + (size_t)sm.r0 * D * e;
-      char *us = u + (size_t)sm.r0 * F * e;
+      const int nr = B * sm.seg;
+      float *xs = xbuf + sm.r0 * D;
+      const float *xs_in = xsrc + sm.r0 * D;   // differs from xs only before the first update
+      char *hs = h + sm.r0 * D * e;
+      char *as = a + sm.r0 * D * e;
+      char *us = u + sm.r0 * F * e;
       const bool xattn = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
       char *xb = xattn ? ws + w.xb : nullptr;
-      PF_TRY(gemm(s, PF_KC_GEMM_OUT, as, D, sm.lw->w_o, D, sm.lw->b_o, xs, D, sm.nr, D, D, 1, 0, sm.m + 2 * D, xs_in, D, xb, D));
+      PF_TRY(gemm(s, PF_KC_GEMM_OUT, as, D, sm.lw->w_o, D, sm.lw->b_o, xs, D, nr, D, D, 1, 0, sm.m + 2 * D, xs_in, D, xb, D, nullptr, sm.seg));
       if (xattn) {
         char *qc = ws + w.qc;
-        PF_TRY(gemm(s, PF_KC_GEMM_XATTN, xb, D, sm.lw->xattn_wq, D, sm.lw->xattn_bq, qc, D, sm.nr, D, D, 0, D, nullptr, nullptr, 0, nullptr, 0));
-        PF_TRY(attention(s, PF_KC_XATTN, qc, D, s->kcptr(l), s->vcptr(l), d.T, d.Tp, as, D, sm.nr));
-        PF_TRY(gemm(s, PF_KC_GEMM_XATTN, as, D, sm.lw->xattn_wo, D, sm.lw->xattn_bo, xs, D, sm.nr, D, D, 1, 0, nullptr, xs, D, nullptr, 0));
+        PF_TRY(gemm(s, PF_KC_GEMM_XATTN, xb, D, sm.lw->xattn_wq, D, sm.lw->xattn_bq, qc, D, nr, D, D, 0, D, nullptr, nullptr, 0, nullptr, 0));
+        PF_TRY(attention(s, PF_KC_XATTN, qc, D, s->kcptr(l), s->vcptr(l), d.T, d.Tp, as, D, sm.seg));
+        PF_TRY(gemm(s, PF_KC_GEMM_XATTN, as, D, sm.lw->xattn_wo, D, sm.lw->xattn_bo, xs, D, nr, D, D, 1, 0, nullptr, xs, D, nullptr, 0));
       }
-      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m + 3 * D, sm.m + 4 * D, c.ln_eps, hs, D, sm.nr, D, 1, st); }));
-      PF_TRY(gemm(s, PF_KC_GEMM_UP, hs, D, sm.lw->w_up, D, sm.lw->b_up, us, F, sm.nr, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
-      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, us, F, sm.lw->w_down, F, sm.lw->b_down, xs, D, sm.nr, D, F, 1, 0, sm.m + 5 * D, xs, D, nullptr, 0));
+      PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m + 3 * D, sm.m + 4 * D, c.ln_eps, hs, D, nr, D, 1, st, B > 1 ? sm.seg : 0, mstride); }));
+      PF_TRY(gemm(s, PF_KC_GEMM_UP, hs, D, sm.lw->w_up, D, sm.lw->b_up, us, F, nr, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
+      PF_TRY(gemm(s, PF_KC_GEMM_DOWN, us, F, sm.lw->w_down, F, sm.lw->b_down, xs, D, nr, D, F, 1, 0, sm.m + 5 * D, xs, D, nullptr, 0, nullptr, sm.seg));
     }
     xsrc = xbuf;   // every stream of this layer has written its rows
   }
 
-  if (y_img && xbuf != y_img) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(y_img, xres + (size_t)Tt * D, (size_t)n_img * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
-  if (Tt && text_out) PF_TRY(run(s, PF_KC_COPY, [&] { return hipMemcpyAsync(text_out, xres, (size_t)Tt * D * sizeof(float), hipMemcpyDeviceToDevice, st); }));
+  if (y_img && xbuf != y_img)
+    PF_TRY(run(s, PF_KC_COPY, [&] { return copy_blocks(y_img, (size_t)n_img * D, xres + i_row0 * D, i_pitch * D, (size_t)n_img * D, B, st); }));
+  if (Tt && text_out)
+    PF_TRY(run(s, PF_KC_COPY, [&] { return copy_blocks(text_out, (size_t)Tt * D, xres + t_row0 * D, t_pitch * D, (size_t)Tt * D, B, st); }));
   return PF_OK;
 }
 
@@ -467,10 +519,14 @@ pf_status pf_kv_init(pf_stage *s, const float *x_prev, const pf_cond *cp, float 
     char *qkv = s->ws + s->w.qkv;
     for (int l = 0; l < c.n_layers; ++l) {
       const pf_layer_weights &lw = s->img[l];
+      // text features of all images, [B][T][cross_dim], in one GEMM; then one scatter per image
       PF_TRY(gemm(s, PF_KC_GEMM_XATTN, cp->text, c.cross_dim, lw.xattn_wkv, c.cross_dim, lw.xattn_bkv, qkv + (size_t)D * d.esz,
-                  3 * D, d.T, 2 * D, c.cross_dim, 0, 2 * D, nullptr, nullptr, 0, nullptr, 0));
-      ScatterArgs sa{c.dtype, qkv, 3 * D, s->kcptr(l), s->vcptr(l), d.Tp, c.n_heads, c.head_dim, 0, d.T, 0, -1, c.grid_w, c.rope_theta};
-      PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, s->stream); }));
+                  3 * D, d.B * d.T, 2 * D, c.cross_dim, 0, 2 * D, nullptr, nullptr, 0, nullptr, 0));
+      for (int b = 0; b < d.B; ++b) {
+        ScatterArgs sa{c.dtype, qkv + (size_t)b * d.T * 3 * D * d.esz, 3 * D, s->kcptr(l) + b * s->ximg_elems() * d.esz,
+                       s->vcptr(l) + b * s->ximg_elems() * d.esz, d.Tp, c.n_heads, c.head_dim, 0, d.T, 0, -1, c.grid_w, c.rope_theta};
+        PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, s->stream); }));
+      }
     }
   }
   if (x_prev) {
@@ -494,14 +550,15 @@ pf_status pf_stage_patch_forward(pf_stage *s, const float *x_patch, const pf_con
                  y_patch, joint_text ? cond->text_out : nullptr);
 }
 
-static pf_status fill_view(const pf_stage *s, int layer, bool cross, pf_kv_view_t *out) {
+static pf_status fill_view(const pf_stage *s, int layer, int image, bool cross, pf_kv_view_t *out) {
   if (!s || !out) return PF_ERR_NULL;
-  if (layer < 0 || layer >= s->cfg.n_layers) return PF_ERR_RANGE;
+  if (layer < 0 || layer >= s->cfg.n_layers || image < 0 || image >= s->d.B) return PF_ERR_RANGE;
   if (cross && s->cfg.kind != PF_BLOCK_ADALN_SINGLE_XATTN) return PF_ERR_CONFIG;
   const int dh = s->cfg.head_dim;
   const int rp = cross ? s->d.Tp : s->d.Lp;
-  out->k = cross ? s->kcptr(layer) : s->kptr(layer);
-  out->v = cross ? s->vcptr(layer) : s->vptr(layer);
+  const size_t ioff = (size_t)image * (cross ? s->ximg_elems() : s->img_elems()) * s->d.esz;
+  out->k = (cross ? s->kcptr(layer) : s->kptr(layer)) + ioff;
+  out->v = (cross ? s->vcptr(layer) : s->vptr(layer)) + ioff;
   out->rows = cross ? s->d.T : s->d.Lkv;
   out->rows_padded = rp;
   out->text_rows = cross ? 0 : s->d.Tj;
@@ -511,8 +568,11 @@ static pf_status fill_view(const pf_stage *s, int layer, bool cross, pf_kv_view_
   return PF_OK;
 }
 
-pf_status pf_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, false, out); }
-pf_status pf_xattn_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, true, out); }
+pf_status pf_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, 0, false, out); }
+pf_status pf_xattn_kv_view(const pf_stage *s, int layer, pf_kv_view_t *out) { return fill_view(s, layer, 0, true, out); }
+pf_status pf_kv_view_image(const pf_stage *s, int layer, int image, int cross, pf_kv_view_t *out) {
+  return fill_view(s, layer, image, cross != 0, out);
+}
 
 pf_status pf_stage_attention_plan(const pf_stage *s, int nq, int cross, int *splits, size_t *ws_needed,
                                   size_t *ws_reserved) {
@@ -520,7 +580,7 @@ pf_status pf_stage_attention_plan(const pf_stage *s, int nq, int cross, int *spl
   if (nq < 1 || nq > s->d.Lkv) return PF_ERR_RANGE;
   if (cross && s->cfg.kind != PF_BLOCK_ADALN_SINGLE_XATTN) return PF_ERR_CONFIG;
   *splits = plan_splits(s, nq, cross ? s->d.T : s->d.Lkv);
-  *ws_needed = attention_ws_bytes(nq, s->cfg.n_heads, s->cfg.head_dim, *splits);
+  *ws_needed = attention_ws_bytes(nq, s->cfg.n_heads * s->d.B, s->cfg.head_dim, *splits);
   *ws_reserved = s->w.attn_bytes;
   return PF_OK;
 }

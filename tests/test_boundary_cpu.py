@@ -47,6 +47,39 @@ def test_kv_bytes_is_full_sequence_kv_for_own_layers(lib):
         assert lib.pf_stage_workspace_bytes(C.byref(c)) > 0
 
 
+def test_batch_multiplies_the_kv_buffer_and_limits(lib):
+    """Every image of a batched call has K/V buffers of its own; batch 0 and 1 both mean one image."""
+    for name in ("C2", "C3", "K3f"):
+        cfg = wl.CONFIGS[name]
+        one = lib.pf_stage_kv_bytes(C.byref(B.make_config(cfg)))
+        assert lib.pf_stage_kv_bytes(C.byref(B.make_config(dict(cfg, batch=0)))) == one
+        for b in (2, 3, 8):
+            assert lib.pf_stage_kv_bytes(C.byref(B.make_config(dict(cfg, batch=b)))) == b * one
+            assert lib.pf_stage_workspace_bytes(C.byref(B.make_config(dict(cfg, batch=b)))) > \
+                lib.pf_stage_workspace_bytes(C.byref(B.make_config(cfg)))
+        for b in (-1, 9):
+            assert lib.pf_stage_kv_bytes(C.byref(B.make_config(dict(cfg, batch=b)))) == 0
+
+
+def test_batched_views_and_plan(lib):
+    cfg = dict(wl.CONFIGS["C2"], batch=2)
+    st, h = _fake_stage(lib, cfg)
+    assert st == 0
+    v0, v1, vx = B.PfKvView(), B.PfKvView(), B.PfKvView()
+    assert lib.pf_kv_view_image(h, 0, 0, 0, C.byref(v0)) == 0
+    assert lib.pf_kv_view_image(h, 0, 1, 0, C.byref(v1)) == 0
+    Lp = (wl.kv_rows(cfg) + 127) // 128 * 128
+    assert v1.k - v0.k == Lp * cfg["hidden"] * 2 and v1.v - v0.v == Lp * cfg["hidden"] * 2
+    assert v0.v - v0.k == 2 * Lp * cfg["hidden"] * 2          # both images' K come before the first V^T
+    assert lib.pf_kv_view_image(h, 0, 2, 0, C.byref(vx)) == -6
+    assert lib.pf_kv_view_image(h, 0, 1, 1, C.byref(vx)) == 0
+    for nq in (wl.patch_rows(cfg), cfg["seq_img"]):
+        sp, need, res = C.c_int(), C.c_size_t(), C.c_size_t()
+        assert lib.pf_stage_attention_plan(h, nq, 0, C.byref(sp), C.byref(need), C.byref(res)) == 0
+        assert need.value <= res.value
+    lib.pf_stage_destroy(h)
+
+
 BAD = [dict(hidden=100), dict(n_patches=7), dict(head_dim=12, n_heads=32), dict(dtype_code=5), dict(kind=9),
        dict(grid_w=3), dict(mlp_dim=100), dict(n_layers=0), dict(ln_eps=0.0)]
 
