@@ -2,7 +2,7 @@
 stage's patch call for several patch counts M, and the full sampling-loop step (all M patches through N chained stages plus
 the update) for one of them.  Prints one JSON line per measurement.
 
-  python -m paper_2405_14430_amd.sweep --workload C2 --patches 2 4 8 16 32 [--stages 2] [--iters 50]
+  python -m paper_2405_14430_amd.sweep --workload C2 --patches 2 4 8 16 32 [--stages 2] [--batch 1 2] [--iters 50]
 
 On N devices one micro-step costs max over stages of (patch call + P2P); a smaller patch shortens the pipeline fill
 (N - 1 micro-steps) but makes every operator smaller.  The sweep shows the second half on one device: tokens/s of the stage
@@ -80,6 +80,43 @@ def sweep_patch_call(name, patches, iters, warmup):
         del st
 
 
+def sweep_batch(name, batches, iters, warmup):
+    """Patch call of the workload at its own M for B images per call (B = 2: the conditional and unconditional image of
+    classifier-free guidance share one call, Sec. 4.1.3 runs them on separate device groups instead)."""
+    import torch
+    from . import Stage
+    base = wl.CONFIGS[name]
+    W = wl.make_weights(base)
+    M, n = base["n_patches"], wl.patch_rows(base)
+    for B in batches:
+        acts = [wl.make_activations(wl.variant(base, seed=base["seed"] + 100 * b)) for b in range(B)]
+        stack = lambda k: _dev(np.stack([a[k] for a in acts], 0))
+        cfg = dict(base, batch=B)
+        cond, x, xprev = stack("cond"), stack("x"), stack("x_prev")
+        text = None
+        if acts[0]["text"] is not None:
+            text = stack("text")
+            if base["kind"] == 1:
+                text = text.to(torch.bfloat16 if base["dtype"] == "bf16" else torch.float32)
+        st = Stage(cfg, W)
+        st.kv_init(xprev, cond, text)
+        xs = [x[:, p * n:(p + 1) * n].contiguous() for p in range(M)]
+        y = torch.empty_like(xs[0])
+        for i in range(warmup):
+            st.patch_forward(xs[i % M], cond, i % M, out=y)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(iters):
+            st.patch_forward(xs[i % M], cond, i % M, out=y)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / iters
+        print(json.dumps({"what": "batched_patch_call", "workload": name, "batch": B, "n_patches": M, "patch_tokens": n,
+                          "ms_per_call": ms, "tokens_per_s": B * n / (ms * 1e-3),
+                          "tflops": B * call_flops(base, n) / (ms * 1e-3) / 1e12}), flush=True)
+        st.destroy()
+        del st
+
+
 def time_full_step(name, M, n_stages, steps):
     """One diffusion step after warm-up on one device: M patches x N stages + the update."""
     import torch
@@ -119,12 +156,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--stages", type=int, default=0, help="> 0: also time the full sampling-loop step with this many stages")
     ap.add_argument("--steps", type=int, default=4)
+    ap.add_argument("--batch", type=int, nargs="*", default=[], help="also time the patch call for these images-per-call")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         print("sweep: no GPU visible", file=sys.stderr)
         sys.exit(1)
     sweep_patch_call(args.workload, args.patches, args.iters, args.warmup)
+    if args.batch:
+        sweep_batch(args.workload, args.batch, args.iters, args.warmup)
     if args.stages > 0:
         time_full_step(args.workload, wl.CONFIGS[args.workload]["n_patches"], args.stages, args.steps)
 
