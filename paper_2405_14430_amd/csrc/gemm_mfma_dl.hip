@@ -556,11 +556,6 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
     case 26: return launch_tile<64, 64, 3>(a, s);
     case 27: return launch_tile<128, 64, 3>(a, s);
-    case 28: return launch_tile<64, 64, 6>(a, s);
-    case 29: return launch_tile<64, 64, 8>(a, s);
-    case 30: return launch_tile<64, 64, 5>(a, s);
-    case 31: return launch_tile<128, 64, 6>(a, s);
-    case 32: return launch_tile<128, 64, 5>(a, s);
     default: break;
   }
   switch (pick_variant(a)) {

@@ -119,7 +119,7 @@ def test_gemm_gated_residual_epilogue(dtype, path, M, N, K):
     assert _close(x2, R.astype(np.float64) + po.linear(A, W, b), dtype)
 
 
-@pytest.mark.parametrize("tile_id", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18])
+@pytest.mark.parametrize("tile_id", list(range(1, 28)))
 def test_gemm_every_tile_configuration(tile_id):
     """Each bf16 tile configuration the heuristic can pick (and the ones it currently does not), pinned through the
     tuning hook, on a shape with ragged M and N, for both epilogues."""
@@ -141,6 +141,24 @@ def test_gemm_every_tile_configuration(tile_id):
     refx = R.astype(np.float64) + gate.astype(np.float64) * ref
     ref[:, 320:] = po.gelu(ref[:, 320:], True)
     assert _close(got, ref, BF) and _close(x, refx, BF) and torch.equal(xb, x.to(BF))
+
+
+@pytest.mark.parametrize("tile_id", [5, 26, 1, 10])
+@pytest.mark.parametrize("K", [64, 128, 192])
+def test_gemm_rings_on_short_k(tile_id, K):
+    """Fewer K tiles than ring stages: prologue and drain only."""
+    pkg = _pkg()
+    lib = pkg.load_library()
+    M, N = 130, 200
+    rng = _rng(999 + tile_id + K)
+    A, W, b = _draw(rng, (M, K), BF), _draw(rng, (N, K), BF, 1 / math.sqrt(K)), _draw(rng, (N,), BF)
+    lib.pf_tune_gemm_tile(tile_id)
+    try:
+        got = pkg.pf_op_gemm(_dev(A, BF), _dev(W, BF), _dev(b, BF), epilogue=0)
+        torch.cuda.synchronize()
+    finally:
+        lib.pf_tune_gemm_tile(0)
+    assert _close(got, po.linear(A, W, b), BF)
 
 
 def test_gemm_erf_gelu():
