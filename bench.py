@@ -96,9 +96,10 @@ def main():
     text = None
     if A["text"] is not None:
         text = dev(A["text"]).to(dt) if cfg["kind"] == 1 else dev(A["text"])
+    from paper_2405_14430_amd import load_library
+    for t in args.tune:      # before the stage exists: its workspace is sized from the launch plans the hooks change
+        load_library().pf_tune_gemm_tile(t)
     st = Stage(cfg, W, kernel_path=args.path)
-    for t in args.tune:
-        st.lib.pf_tune_gemm_tile(t)
     st.kv_init(dev(A["x_prev"]), cond, text)
     x = dev(A["x"])
     xs = [x[p * n:(p + 1) * n].contiguous() for p in range(M)]

@@ -510,11 +510,24 @@ int g_wavek_max_tiles = 512;    // tuning hook: it takes GEMMs with fewer 64 x 6
 //    192 tiles, K = 15360) prefer it too, with 64-wide stages;
 //  * 128x128 (two workgroups per CU) from about 1.5 workgroups per CU, then 128x64;
 //  * skinny GEMMs (n = 512 patch rows): 64x64 tiles with the deepest ring that still lets every workgroup be resident
-//    at once (4 stages: 2 per CU, 3 stages: 3 per CU), and the K-splitting kernel when K is long and tiles are few.
-enum { V_256x256 = 0, V_256x128_K32S3, V_256x128_S3, V_128x128, V_128x64, V_WAVEK, V_64x64_S4, V_64x64_S3, V_64x64_S2, V_COUNT };
+//    at once (4 stages: 2 per CU, 3 stages: 3 per CU), and the K-splitting kernel when K is long and tiles are few;
+//  * 192-wide tiles (three 32-column blocks per wave) when they cut the output into a whole number of 256-workgroup
+//    rounds, which power-of-two tiles cannot do for widths that are multiples of 3 * 1024 (Flux-scale stage, patch of
+//    2048 rows: QKV 171 -> 144 us with 768 tiles of 128x192, MLP-up 178 -> 172 us with 512 tiles of 256x192, MLP-down
+//    241 -> 214 us with 256 tiles of 128x192 and three stages); not for K = 1152, where the two-stage ring is exposed.
+enum { V_256x256 = 0, V_256x128_K32S3, V_256x128_S3, V_128x128, V_128x64, V_WAVEK, V_64x64_S4, V_64x64_S3, V_64x64_S2,
+       V_128x192_S2, V_256x192_S2, V_128x192_S3, V_COUNT };
 
 static int pick_variant(const GemmArgs &a) {
   auto tiles = [&](int bm, int bn) { return (int64_t)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+  if (a.N % 192 == 0 && a.M % 128 == 0) {
+    const int64_t t192 = tiles(128, 192);
+    if (a.K >= 4096 && t192 >= 128 && t192 <= 256) return V_128x192_S3;
+    if (a.K >= 2048 && t192 % 256 == 0 && t192 <= 1024) {
+      const int64_t t2 = a.M % 256 == 0 ? tiles(256, 192) : 0;
+      return (t2 >= 512 && t2 % 256 == 0) ? V_256x192_S2 : V_128x192_S2;
+    }
+  }
   if (tiles(256, 256) >= 1024) return V_256x256;
   if (tiles(256, 128) >= 512) return V_256x128_K32S3;
   if (a.K >= 8192 && tiles(256, 128) >= 128) return V_256x128_S3;
@@ -556,6 +569,9 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
     case 26: return launch_tile<64, 64, 3>(a, s);
     case 27: return launch_tile<128, 64, 3>(a, s);
+    case 28: return launch_tile<128, 192, 2>(a, s);
+    case 29: return launch_tile<256, 192, 2, 4, 2>(a, s);
+    case 30: return launch_tile<128, 192, 3>(a, s);
     default: break;
   }
   switch (pick_variant(a)) {
@@ -567,6 +583,9 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case V_WAVEK: return launch_wavek<64, 64>(a, s);
     case V_64x64_S4: return launch_tile<64, 64, 4>(a, s);
     case V_64x64_S3: return launch_tile<64, 64, 3>(a, s);
+    case V_128x192_S2: return launch_tile<128, 192, 2>(a, s);
+    case V_256x192_S2: return launch_tile<256, 192, 2, 4, 2>(a, s);
+    case V_128x192_S3: return launch_tile<128, 192, 3>(a, s);
     default: return launch_tile<64, 64, 2>(a, s);
   }
 }
@@ -576,7 +595,8 @@ const char *gemm_mfma_dl_variant_name(const GemmArgs &a) {
                                        "gemm_tile_kernel<256,128,3,4,2,64>", "gemm_tile_kernel<128,128,2,2,2,64>",
                                        "gemm_tile_kernel<128,64,2,2,2,64>", "gemm_wavek_kernel<64,64>",
                                        "gemm_tile_kernel<64,64,4,2,2,64>", "gemm_tile_kernel<64,64,3,2,2,64>",
-                                       "gemm_tile_kernel<64,64,2,2,2,64>"};
+                                       "gemm_tile_kernel<64,64,2,2,2,64>", "gemm_tile_kernel<128,192,2,2,2,64>",
+                                       "gemm_tile_kernel<256,192,2,4,2,64>", "gemm_tile_kernel<128,192,3,2,2,64>"};
   return names[pick_variant(a)];
 }
 

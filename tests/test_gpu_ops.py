@@ -119,7 +119,7 @@ def test_gemm_gated_residual_epilogue(dtype, path, M, N, K):
     assert _close(x2, R.astype(np.float64) + po.linear(A, W, b), dtype)
 
 
-@pytest.mark.parametrize("tile_id", list(range(1, 28)))
+@pytest.mark.parametrize("tile_id", list(range(1, 31)))
 def test_gemm_every_tile_configuration(tile_id):
     """Each bf16 tile configuration the heuristic can pick (and the ones it currently does not), pinned through the
     tuning hook, on a shape with ragged M and N, for both epilogues."""
