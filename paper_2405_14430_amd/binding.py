@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpfstage.so")
+LIB_PATH = os.environ.get("PFSTAGE_LIB") or os.path.join(_HERE, "libpfstage.so")   # override: another build of the library
 
 PF_F32, PF_BF16 = 0, 1
 PF_PATH_AUTO, PF_PATH_SIMT = 0, 1
