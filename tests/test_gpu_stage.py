@@ -221,3 +221,37 @@ def test_state_and_argument_errors():
         st.patch_forward(x, cond, cfg["n_patches"])
     assert e.value.status == -6
     st.destroy()
+
+
+def test_patch_call_under_graph_capture_replays_exactly():
+    """The library enqueues only kernels and device-to-device copies on the stage's stream, so a patch call can be
+    captured into a HIP graph.  Every replay (with eager work and synchronisations in between) must give the bits
+    of the eager call."""
+    cfg = wl.CONFIGS["C2s"]
+    W, A = wl.make_weights(cfg), wl.make_activations(cfg)
+    st = _pkg().Stage(cfg, W)
+    cond, text = _f32(A["cond"]), _text_dev(cfg, A)
+    st.kv_init(_f32(A["x_prev"]), cond, text)
+    n, p = wl.patch_rows(cfg), 2
+    x = _f32(A["x"][p * n:(p + 1) * n])
+    eager = st.patch_forward(x, cond, p).clone()
+    torch.cuda.synchronize()
+    y = torch.empty_like(eager)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        st.set_stream(torch.cuda.current_stream())
+        st.patch_forward(x, cond, p, out=y)
+    st.set_stream(torch.cuda.current_stream())
+    for i in range(4):
+        # eager work between the replays: another patch (changes the buffer rows patch p attends to), then the
+        # reference call for patch p on that state
+        q = i % 2
+        st.patch_forward(_f32(A["x"][q * n:(q + 1) * n]) * (1.0 + 0.1 * i), cond, q)
+        eager = st.patch_forward(x, cond, p).clone()
+        torch.cuda.synchronize()
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager), f"replay {i} differs from the eager call"
+    st.destroy()
