@@ -128,11 +128,18 @@ def main():
         step(i)
     prof = st.profile_read()
     st.profile(0)
+    # An event between two launches costs GPU time of its own.  The cost per launch is measured live: what the event
+    # intervals of a step add up to, minus the step time of the pass without events, over the launches of a step.
+    total_ms = sum(ms for ms, cnt in prof.values()) / args.steps
+    total_launches = sum(cnt for ms, cnt in prof.values()) / args.steps
+    event_overhead_us = max(0.0, (total_ms - ms_per_step) / max(total_launches, 1.0) * 1e3)
     kernels = {}
     for cls, (ms, cnt) in prof.items():
         if cnt:
-            kernels[cls] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
-                            "avg_us": ms / cnt * 1e3}
+            raw = ms / cnt * 1e3
+            kernels[cls] = {"ms_per_step": (raw - event_overhead_us) * cnt / args.steps * 1e-3,
+                            "launches_per_step": cnt / args.steps, "avg_us": raw - event_overhead_us,
+                            "avg_us_with_event": raw}
     peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_F32_TFLOPS
     for c in kernels:
         f = flops_per_launch(cfg, c, n)
@@ -174,7 +181,7 @@ def main():
     roofline = {"kernel": dom, "classes": g["classes"], "bound": "mfma" if cfg["dtype"] == "bf16" else "alu",
                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
                 "avg_launch_us": g["ms"] / g["launches"] * 1e3, "launches_per_step": g["launches"],
-                "flops_per_launch": g["flops"] / g["launches"]}
+                "flops_per_launch": g["flops"] / g["launches"], "event_overhead_us": event_overhead_us}
 
     cpu = None
     if not args.no_cpu:

@@ -210,11 +210,12 @@ pf_status pf_stage_attention_plan(const pf_stage *stage, int nq, int cross, int 
 pf_status pf_stage_set_stream(pf_stage *stage, void *hip_stream);
 
 /*
- * Per-kernel-class timing with HIP events on the stage's stream.  After pf_stage_profile(stage, 1) every
- * kernel launch of the stage is bracketed by an event pair; pf_stage_profile_read synchronises the
- * stream, adds up the elapsed time per class since the last read and resets.  Classes: see
- * pf_kernel_class.  Event pairs cost a few microseconds per launch: use a separate pass from the one
- * that measures whole-call throughput.  ms and launches are host arrays of PF_KC_COUNT entries.
+ * Per-kernel-class timing with HIP events on the stage's stream.  After pf_stage_profile(stage, 1) an event
+ * is recorded before the first launch of every call and after each launch (consecutive launches share the
+ * event between them); pf_stage_profile_read synchronises the stream, adds up the elapsed time per class
+ * since the last read and resets.  Classes: see pf_kernel_class.  An event costs a microsecond or two per
+ * launch: use a separate pass from the one that measures whole-call throughput.  ms and launches are host
+ * arrays of PF_KC_COUNT entries.
  */
 typedef enum {
   PF_KC_MODULATION = 0, PF_KC_LN_MODULATE, PF_KC_GEMM_QKV, PF_KC_KV_SCATTER, PF_KC_ATTENTION,

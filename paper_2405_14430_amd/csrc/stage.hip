@@ -170,9 +170,13 @@ struct pf_stage {
   std::string err;
   // profiling
   bool prof = false;
-  struct Ev { int cls; hipEvent_t a, b; };
-  std::vector<Ev> events;
+  // A mark is an event recorded on the stream; a launch of class cls spans the mark before it and its own mark
+  // (cls < 0: start of a chain of launches).  Consecutive launches share the mark between them, so profiling adds one
+  // event per launch, not two.
+  struct Mark { int cls; hipEvent_t ev; };
+  std::vector<Mark> events;
   std::vector<hipEvent_t> pool;
+  bool chain_open = false;
 
   // Layer l of the caller's K/V buffer: [K of image 0 .. B-1][V^T of image 0 .. B-1][cross K ...][cross V^T ...], each
   // image's part head-major.  img_elems / ximg_elems: elements between consecutive images.
@@ -207,11 +211,16 @@ hipEvent_t get_event(pf_stage *s) {
 template <typename Fn>
 hipError_t run(pf_stage *s, int cls, Fn &&fn) {
   if (!s->prof) return fn();
-  pf_stage::Ev ev{cls, get_event(s), get_event(s)};
-  (void)hipEventRecord(ev.a, s->stream);
+  if (!s->chain_open) {
+    pf_stage::Mark m{-1, get_event(s)};
+    (void)hipEventRecord(m.ev, s->stream);
+    s->events.push_back(m);
+    s->chain_open = true;
+  }
   hipError_t e = fn();
-  (void)hipEventRecord(ev.b, s->stream);
-  s->events.push_back(ev);
+  pf_stage::Mark m{cls, get_event(s)};
+  (void)hipEventRecord(m.ev, s->stream);
+  s->events.push_back(m);
   return e;
 }
 
@@ -512,6 +521,7 @@ pf_status pf_kv_init(pf_stage *s, const float *x_prev, const pf_cond *cp, float 
     if (d.Tj && !cp->text) return fail(s, PF_ERR_NULL, "joint kinds: warm-up pass needs cond_prev->text");
   }
   s->err.clear();
+  s->chain_open = false;   // other work may have been enqueued on the stream since the last call
   PF_TRY(run(s, PF_KC_COPY, [&] { return launch_fill_zero(s->kv, kv_layer_bytes(&c, d) * c.n_layers, s->stream); }));
   if (c.kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
     // text keys/values of every layer's cross-attention, computed once
@@ -546,6 +556,7 @@ pf_status pf_stage_patch_forward(pf_stage *s, const float *x_patch, const pf_con
   const bool joint_text = s->d.Tj && cond->text;
   if (joint_text && !cond->text_out) return fail(s, PF_ERR_NULL, "text rows given without text_out");
   s->err.clear();
+  s->chain_open = false;   // other work may have been enqueued on the stream since the last call
   return forward(s, x_patch, s->d.n, patch_idx * s->d.n, cond->cond, joint_text ? (const float *)cond->text : nullptr,
                  y_patch, joint_text ? cond->text_out : nullptr);
 }
@@ -594,6 +605,7 @@ pf_status pf_stage_set_stream(pf_stage *s, void *hip_stream) {
 pf_status pf_stage_profile(pf_stage *s, int enable) {
   if (!s) return PF_ERR_NULL;
   s->prof = enable != 0;
+  s->chain_open = false;
   return PF_OK;
 }
 
@@ -602,19 +614,23 @@ pf_status pf_stage_profile_read(pf_stage *s, double *ms, int64_t *launches) {
   for (int i = 0; i < PF_KC_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
   if (s->events.empty()) return PF_OK;
   PF_TRY(hipStreamSynchronize(s->stream));
-  for (auto &ev : s->events) {
+  for (size_t i = 0; i < s->events.size(); ++i) {
+    const pf_stage::Mark &m = s->events[i];
     float t = 0.f;
-    if (hipEventElapsedTime(&t, ev.a, ev.b) == hipSuccess) { ms[ev.cls] += t; launches[ev.cls] += 1; }
-    s->pool.push_back(ev.a);
-    s->pool.push_back(ev.b);
+    if (m.cls >= 0 && i > 0 && hipEventElapsedTime(&t, s->events[i - 1].ev, m.ev) == hipSuccess) {
+      ms[m.cls] += t;
+      launches[m.cls] += 1;
+    }
   }
+  for (auto &m : s->events) s->pool.push_back(m.ev);
   s->events.clear();
+  s->chain_open = false;
   return PF_OK;
 }
 
 void pf_stage_destroy(pf_stage *s) {
   if (!s) return;
-  for (auto &ev : s->events) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+  for (auto &m : s->events) (void)hipEventDestroy(m.ev);
   for (auto e : s->pool) (void)hipEventDestroy(e);
   delete s;
 }
