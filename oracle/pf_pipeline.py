@@ -86,3 +86,23 @@ class PipelineOracle:
             trace.append(eps)
             x = euler_update(x, eps, dt)
         return x, trace
+
+
+# --------------------------------------------------------------------------- #
+# cost model of the parallel schemes (Sec. 3.4, Table 1)                       #
+# --------------------------------------------------------------------------- #
+def scheme_costs(scheme, p, hs, L, N, kv_bytes_per_layer, param_bytes):
+    """Per-device cost of one diffusion step as the table of Sec. 3.4 states it (orders of magnitude, constants as
+    printed): communicated elements, whether the communication overlaps with compute, parameter bytes and K/V
+    activation bytes held.  p = sequence length, hs = hidden size, L = layers, N = devices;
+    kv_bytes_per_layer = bytes of full-sequence K and V of one layer."""
+    KV = kv_bytes_per_layer
+    rows = {
+        "tensor_parallel": (4 * p * hs * L, False, param_bytes / N, KV / N),
+        "distrifusion":    (2 * p * hs * L, True, param_bytes, KV * L),
+        "sp_ring":         (2 * p * hs * L, True, param_bytes, KV / N),
+        "sp_ulysses":      (4 * p * hs * L / N, False, param_bytes, KV / N),
+        "pipefusion":      (2 * p * hs, True, param_bytes / N, KV * L / N),
+    }
+    comm, overlap, params, kv = rows[scheme]
+    return {"comm_elements": comm, "overlap": overlap, "param_bytes": params, "kv_bytes": kv}

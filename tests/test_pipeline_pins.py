@@ -148,3 +148,28 @@ def test_euler_update_is_linear():
     assert np.array_equal(pp.euler_update(x, e, 0.0), x)
     assert np.allclose(pp.euler_update(x, e, -0.25), x - 0.25 * e, rtol=0, atol=0)
     assert np.allclose(pp.euler_update(pp.euler_update(x, e, 0.1), e, 0.2), pp.euler_update(x, e, 0.3), atol=1e-15)
+
+
+def test_cost_table_relations_and_library_buffer_size():
+    """Sec. 3.4, Table 1: PipeFusion's traffic does not grow with the layer count, DistriFusion keeps the K/V of all L
+    layers on every device, PipeFusion (1/N) of that; and the library's per-stage K/V buffer is exactly that entry
+    (up to the padding of the row count to 128)."""
+    import ctypes as C
+    from paper_2405_14430_amd import binding as B
+    cfg = wl.CONFIGS["C2"]
+    p, hs, N = cfg["seq_img"], cfg["hidden"], 7
+    Ltot = cfg["n_layers"] * N                      # C2 is one of N = 7 stages of a 28-layer model
+    kv_layer = 2 * p * hs * 2                       # full-sequence K and V of one layer, bf16
+    pf_ = pp.scheme_costs("pipefusion", p, hs, Ltot, N, kv_layer, 1.0)
+    df = pp.scheme_costs("distrifusion", p, hs, Ltot, N, kv_layer, 1.0)
+    tp = pp.scheme_costs("tensor_parallel", p, hs, Ltot, N, kv_layer, 1.0)
+    assert df["comm_elements"] == Ltot * pf_["comm_elements"] and tp["comm_elements"] == 2 * df["comm_elements"]
+    assert df["kv_bytes"] == N * pf_["kv_bytes"] and pf_["param_bytes"] == df["param_bytes"] / N
+    assert pf_["overlap"] and df["overlap"] and not tp["overlap"]
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2405_14430_amd.build import build
+        build()
+    lib = B.load_library()
+    stage_bytes = lib.pf_stage_kv_bytes(C.byref(B.make_config(cfg)))
+    cross = 2 * 128 * hs * 2 * cfg["n_layers"]      # cached text K/V of the cross-attention (120 keys padded to 128)
+    assert stage_bytes - cross == pf_["kv_bytes"]   # 4096 rows need no padding
