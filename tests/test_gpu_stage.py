@@ -255,3 +255,37 @@ def test_patch_call_under_graph_capture_replays_exactly():
         torch.cuda.synchronize()
         assert torch.equal(y, eager), f"replay {i} differs from the eager call"
     st.destroy()
+
+
+@pytest.mark.parametrize("name,M", [("K0f", 300), ("K3f", 68), ("C2s", 1200), ("C2s", 400), ("C4s", 1500), ("C3s", 360)])
+def test_tiny_patches(name, M):
+    """Degenerate patch sizes: one token per patch (M = L) and three tokens per patch; text rows ride with patch 0 for
+    the joint kinds.  A few patches spread over the sequence are compared with the oracle, and the buffers at the end."""
+    cfg = wl.variant(wl.CONFIGS[name], n_patches=M)
+    tol = TOL[cfg["dtype"]]
+    W, A = wl.make_weights(cfg), wl.make_activations(cfg)
+    n = wl.patch_rows(cfg)
+    _log("tiny patches", name, "M", M, "n", n)
+    st = _pkg().Stage(cfg, W)
+    orc = StageOracle(cfg, W)
+    cond, text = _f32(A["cond"]), _text_dev(cfg, A)
+    joint = cfg["kind"] in (2, 3)
+    st.kv_init(_f32(A["x_prev"]), cond, text)
+    orc.kv_init(A["x_prev"], A["cond"], text=A["text"])
+    for p in (0, 1, M // 2, M - 1):
+        xp = A["x"][p * n:(p + 1) * n]
+        if joint and p == 0:
+            y, yt = st.patch_forward(_f32(xp), cond, p, text=text)
+            ref, reft = orc.patch_forward(xp, A["cond"], p, text=A["text"])
+            assert _relerr(yt, reft) < tol
+        else:
+            y = st.patch_forward(_f32(xp), cond, p)
+            ref = orc.patch_forward(xp, A["cond"], p)
+        torch.cuda.synchronize()
+        err = _relerr(y, ref)
+        _log(f"  patch {p}: err {err:.3e}")
+        assert err < tol
+    for l in range(len(W)):
+        K, V, _ = st.kv_view(l)
+        assert _kv_close(_natural(K), orc.kbuf[l], cfg["dtype"]) and _kv_close(_natural(V), orc.vbuf[l], cfg["dtype"])
+    st.destroy()
