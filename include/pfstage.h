@@ -89,6 +89,12 @@ typedef struct {
                           groups; on one device they share the weights and every GEMM).  Each image has K/V buffers of its
                           own.  With B > 1 every per-call array gains a leading image axis: x_patch / y_patch [B, n, d],
                           x_prev / y_prev [B, L, d], cond [B, d or 6d], text / text_out [B, T, ...]. */
+  int32_t qk_norm;     /* 1: q and k of every head are RMS-normalised over the head's channels (learned scale
+                          q_norm_w / k_norm_w, eps = ln_eps) right after the projection and before any RoPE, as the
+                          Flux-family blocks do (the paper names the models, Sec. 5, not this detail).  head_dim must
+                          be a power of two.  0: off */
+  int32_t joint_rope;  /* kind 2 only, 1: RoPE on q and k of the image rows exactly as in kind 3 (text rows are not
+                          rotated): the two-stream block of Flux-like models.  0: off */
 } pf_config;
 
 #define PF_MAX_BATCH 8
@@ -108,6 +114,8 @@ typedef struct {
  *   kind 1 only: xattn_wq [d, d], xattn_bq [d]; xattn_wkv [2d, cross_dim], xattn_bkv [2d] (keys then
  *                values); xattn_wo [d, d], xattn_bo [d].  Cross-attention reads the un-normalised
  *                residual, has no modulation and no gate, and sits between self-attention and MLP.
+ *   qk_norm only: q_norm_w [dh], k_norm_w [dh]: scales of the per-head RMSNorm (shared by the heads; kind 2: one
+ *                pair per stream).
  *   kind 2 only: txt points to a second pf_layer_weights (host memory, copied at creation) holding the
  *                text stream's weights in the same layout.
  */
@@ -118,6 +126,7 @@ typedef struct pf_layer_weights {
   const void *w_up, *b_up;
   const void *w_down, *b_down;
   const void *xattn_wq, *xattn_bq, *xattn_wkv, *xattn_bkv, *xattn_wo, *xattn_bo;
+  const void *q_norm_w, *k_norm_w;
   const struct pf_layer_weights *txt;
 } pf_layer_weights;
 
@@ -274,11 +283,14 @@ const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K);
  * Row i goes to buffer row row0 + i of K [H][rows_padded][dh] and of V^T [H][dh][rows_padded]; no other
  * buffer element is written.  With rope != 0 the q and k channels of the rows are first rotated in place
  * in qkv (token index tok0 + i on a grid of width grid_w; tok0 < 0: no rotation, used for text rows),
- * and the rotated k is what reaches the buffer.
+ * and the rotated k is what reaches the buffer.  With q_norm_w / k_norm_w != NULL (dtype [head_dim], both or
+ * neither; head_dim a power of two) q and k of every head are first RMS-normalised over the head's channels,
+ * x / sqrt(mean x^2 + norm_eps) * w, before any rotation, also in place.
  */
 pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *vtbuf, int rows_padded,
                            int n_heads, int head_dim, int row0, int rows, int rope, int tok0, int grid_w,
-                           float rope_theta, void *stream);
+                           float rope_theta, const void *q_norm_w, const void *k_norm_w, float norm_eps,
+                           void *stream);
 
 /*
  * out[i][h*dh + c] = sum_j softmax_j(q_i . k_j / sqrt(dh)) v_j[c] over the first `kv_rows` buffer rows.

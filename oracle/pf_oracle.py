@@ -106,6 +106,15 @@ def attention(q, k, v, n_heads, return_probs=False):
     return (out, probs) if return_probs else out
 
 
+def rms_norm_heads(t, w, n_heads, eps):
+    """RMSNorm over the channels of each head: t [n, H*dh] -> t / sqrt(mean_c t^2 + eps) * w, w [dh] shared by heads."""
+    t = np.asarray(t, F64)
+    n, d = t.shape
+    th = t.reshape(n, n_heads, d // n_heads)
+    r = np.sqrt(np.mean(th * th, axis=-1, keepdims=True) + eps)
+    return (th / r * np.asarray(w, F64)).reshape(n, d)
+
+
 def rope_angles(rows, cols, head_dim, theta):
     """Rotation angles [n, head_dim/2] for tokens at grid positions (rows[i], cols[i]).
 
@@ -142,7 +151,9 @@ class StageOracle:
 
     cfg: dict with kind, n_layers, hidden, n_heads, head_dim, mlp_dim, seq_img,
          n_patches, text_len, cross_dim, grid_h, grid_w, ln_eps, rope_theta,
-         gelu_tanh.
+         gelu_tanh; optional qk_norm (RMSNorm of q and k per head, before RoPE,
+         eps = ln_eps, weights q_norm_w / k_norm_w [dh]) and joint_rope (kind 2:
+         RoPE on the image rows as in kind 3).
     layers: list of dicts of arrays, matrices stored [out_features, in_features]:
          w_mod,b_mod, w_qkv,b_qkv, w_o,b_o, w_up,b_up, w_down,b_down,
          xattn_* (kind 1), 'txt' sub-dict (kind 2).
@@ -170,6 +181,8 @@ class StageOracle:
         self.theta = float(cfg.get("rope_theta", 1e4))
         self.gelu_tanh = bool(cfg.get("gelu_tanh", 1))
         self.gw = int(cfg["grid_w"])
+        self.qk_norm = bool(cfg.get("qk_norm", 0))
+        self.joint_rope = bool(cfg.get("joint_rope", 0)) and self.kind == KIND_MMDIT_JOINT
         self.kbuf = [np.zeros((self.Lkv, self.d), F64) for _ in range(self.nl)]
         self.vbuf = [np.zeros((self.Lkv, self.d), F64) for _ in range(self.nl)]
         self.kc = [None] * self.nl     # kind 1: text keys / values of the cross-attention
@@ -222,6 +235,9 @@ class StageOracle:
                 h = ln_modulate(rows, sh, sc, self.eps)
                 qkv = linear(h, w["w_qkv"], w["b_qkv"])
                 q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
+                if self.qk_norm:
+                    q = rms_norm_heads(q, w["q_norm_w"], H, self.eps)
+                    k = rms_norm_heads(k, w["k_norm_w"], H, self.eps)
                 q = self._rope(q, img_tokens)
                 k = self._rope(k, img_tokens)
                 if nt:
@@ -250,6 +266,12 @@ class StageOracle:
                 qkv = linear(h, ws["w_qkv"], ws["b_qkv"])
                 q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
                 is_text = (len(streams) == 2 and si == 0)
+                if self.qk_norm:
+                    q = rms_norm_heads(q, ws["q_norm_w"], H, self.eps)
+                    k = rms_norm_heads(k, ws["k_norm_w"], H, self.eps)
+                if self.joint_rope and not is_text:      # text rows sit at grid position (0, 0): no rotation
+                    q = self._rope(q, img_tokens)
+                    k = self._rope(k, img_tokens)
                 if is_text:
                     self.kbuf[l][: xs.shape[0]] = k
                     self.vbuf[l][: xs.shape[0]] = v

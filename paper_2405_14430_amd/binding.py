@@ -26,7 +26,8 @@ STATUS = {0: "PF_OK", -1: "PF_ERR_NULL", -2: "PF_ERR_CONFIG", -3: "PF_ERR_SHAPE"
 class PfConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("kind", "dtype", "n_layers", "hidden", "n_heads", "head_dim", "mlp_dim",
                                           "seq_img", "n_patches", "text_len", "cross_dim", "grid_h", "grid_w")] + \
-               [("ln_eps", C.c_float), ("rope_theta", C.c_float), ("gelu_tanh", C.c_int32), ("kernel_path", C.c_int32), ("batch", C.c_int32)]
+               [("ln_eps", C.c_float), ("rope_theta", C.c_float), ("gelu_tanh", C.c_int32), ("kernel_path", C.c_int32), ("batch", C.c_int32),
+                ("qk_norm", C.c_int32), ("joint_rope", C.c_int32)]
 
 
 class PfLayerWeights(C.Structure):
@@ -34,7 +35,7 @@ class PfLayerWeights(C.Structure):
 
 
 _W_FIELDS = ["w_mod", "b_mod", "w_qkv", "b_qkv", "w_o", "b_o", "w_up", "b_up", "w_down", "b_down",
-             "xattn_wq", "xattn_bq", "xattn_wkv", "xattn_bkv", "xattn_wo", "xattn_bo"]
+             "xattn_wq", "xattn_bq", "xattn_wkv", "xattn_bkv", "xattn_wo", "xattn_bo", "q_norm_w", "k_norm_w"]
 PfLayerWeights._fields_ = [(n, C.c_void_p) for n in _W_FIELDS] + [("txt", C.POINTER(PfLayerWeights))]
 
 
@@ -107,7 +108,7 @@ def load_library():
     lib.pf_op_gemm.argtypes = [i32, i32, vp, i64, vp, i64, vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, vp, i64,
                                vp, i64, vp]
     lib.pf_op_kv_scatter.restype = i32
-    lib.pf_op_kv_scatter.argtypes = [i32, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, vp]
+    lib.pf_op_kv_scatter.argtypes = [i32, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, f32, vp]
     lib.pf_op_attention_ws_bytes.restype = sz
     lib.pf_op_attention_ws_bytes.argtypes = [i32, i32, i32, i32]
     lib.pf_op_attention.restype = i32
@@ -135,7 +136,8 @@ def make_config(cfg, kernel_path=PF_PATH_AUTO, n_layers=None):
                     seq_img=cfg["seq_img"], n_patches=cfg["n_patches"], text_len=cfg.get("text_len", 0),
                     cross_dim=cfg.get("cross_dim", 0), grid_h=cfg["grid_h"], grid_w=cfg["grid_w"],
                     ln_eps=cfg.get("ln_eps", 1e-6), rope_theta=cfg.get("rope_theta", 1e4),
-                    gelu_tanh=cfg.get("gelu_tanh", 1), kernel_path=kernel_path, batch=cfg.get("batch", 1))
+                    gelu_tanh=cfg.get("gelu_tanh", 1), kernel_path=kernel_path, batch=cfg.get("batch", 1),
+                    qk_norm=cfg.get("qk_norm", 0), joint_rope=cfg.get("joint_rope", 0))
 
 
 def torch_dtype(cfg):
@@ -313,10 +315,11 @@ def pf_op_gemm(A, W, bias, epilogue=0, gelu_from=None, gelu_tanh=1, gate=None, R
 
 
 def pf_op_kv_scatter(qkv, kbuf, vtbuf, rows_padded, n_heads, head_dim, row0, rope=False, tok0=-1, grid_w=1,
-                     theta=1e4):
+                     theta=1e4, q_norm_w=None, k_norm_w=None, norm_eps=1e-6):
     lib = load_library()
     _ok(lib.pf_op_kv_scatter(_dt_code(qkv), _ptr(qkv), qkv.stride(0), _ptr(kbuf), _ptr(vtbuf), rows_padded, n_heads,
-                             head_dim, row0, qkv.shape[0], int(rope), tok0, grid_w, theta, _stream_ptr()))
+                             head_dim, row0, qkv.shape[0], int(rope), tok0, grid_w, theta, _ptr(q_norm_w),
+                             _ptr(k_norm_w), norm_eps, _stream_ptr()))
 
 
 def pf_op_attention(q, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, splits=1, path=PF_PATH_AUTO):

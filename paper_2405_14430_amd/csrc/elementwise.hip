@@ -196,22 +196,36 @@ template <typename T>
 __global__ __launch_bounds__(256) void kv_scatter_kernel(T *__restrict__ qkv, int64_t ld, T *__restrict__ kbuf,
                                                          T *__restrict__ vtbuf, int Lp, int H, int dh, int row0,
                                                          int rows, int rope, int tok0, int grid_w, float theta,
-                                                         int nbk) {
+                                                         int nbk, const T *__restrict__ q_norm_w,
+                                                         const T *__restrict__ k_norm_w, float norm_eps) {
   constexpr int V = Vec16<T>::N;
   const int d = H * dh;
+  const bool norm = q_norm_w != nullptr;
+  const bool inplace = rope || norm;   // q and k are rewritten in qkv (normalised and / or rotated)
   if ((int)blockIdx.x < nbk) {
     const int cpr = d / V;  // chunks per row per part
-    const int parts = rope ? 2 : 1;
+    const int parts = inplace ? 2 : 1;
     int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= (int64_t)rows * parts * cpr) return;
     int i = (int)(id / (parts * cpr));
     int rem = (int)(id % (parts * cpr));
-    int part = rope ? rem / cpr : 1;  // 0 = q, 1 = k
+    int part = inplace ? rem / cpr : 1;  // 0 = q, 1 = k
     int ch = (rem % cpr) * V;         // channel within the part
     T *src = qkv + (size_t)i * ld + (size_t)part * d + ch;
     float v[V];
     Vec16<T>::load(src, v);
     int h = ch / dh, c = ch % dh;
+    if (norm) {
+      // RMSNorm over the head's dh channels: they sit in dh / V consecutive lanes (a power of two, aligned)
+      float ss = 0.f;
+#pragma unroll
+      for (int t = 0; t < V; ++t) ss = fmaf(v[t], v[t], ss);
+      for (int m = 1; m < dh / V; m <<= 1) ss += __shfl_xor(ss, m, 64);
+      const float rinv = rsqrtf(ss / (float)dh + norm_eps);
+      const T *wn = (part == 0 ? q_norm_w : k_norm_w) + c;
+#pragma unroll
+      for (int t = 0; t < V; ++t) v[t] = v[t] * rinv * to_f32(wn[t]);
+    }
     if (rope && tok0 >= 0) {
       int tok = tok0 + i;
       float pr = (float)(tok / grid_w), pc = (float)(tok % grid_w);
@@ -230,13 +244,13 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(T *__restrict__ qkv, in
         v[t + 1] = a * sn + b * cs;
       }
     }
-    if (rope) {
-      Vec16<T>::store(src, v);   // rotated (or, for text rows, unchanged) values stay in qkv
+    if (inplace) {
+      Vec16<T>::store(src, v);   // normalised / rotated (or, for text rows without norm, unchanged) values stay in qkv
       Vec16<T>::load(src, v);    // what reaches the buffer is exactly what qkv now holds
     }
     if (part == 1) {
       T *dst = kbuf + ((size_t)h * Lp + (row0 + i)) * dh + c;
-      if (rope) {
+      if (inplace) {
         Vec16<T>::store(dst, v);
       } else {
         *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
@@ -268,18 +282,20 @@ hipError_t launch_kv_scatter(const ScatterArgs &a, hipStream_t s) {
   if (a.rows <= 0) return hipSuccess;
   const int d = a.n_heads * a.head_dim;
   const int V = a.dt == DT_BF16 ? 8 : 4;
-  int64_t kthreads = (int64_t)a.rows * (a.rope ? 2 : 1) * (d / V);
+  int64_t kthreads = (int64_t)a.rows * ((a.rope || a.q_norm_w) ? 2 : 1) * (d / V);
   int nbk = (int)((kthreads + 255) / 256);
   int nbv = ((a.rows + 63) / 64) * ((d + 63) / 64);
   dim3 g(nbk + nbv);
   if (a.dt == DT_BF16)
     kv_scatter_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t *)a.qkv, a.ld, (bf16_t *)a.kbuf, (bf16_t *)a.vtbuf,
                                                 a.rows_padded, a.n_heads, a.head_dim, a.row0, a.rows, a.rope,
-                                                a.tok0, a.grid_w, a.theta, nbk);
+                                                a.tok0, a.grid_w, a.theta, nbk, (const bf16_t *)a.q_norm_w,
+                                                (const bf16_t *)a.k_norm_w, a.norm_eps);
   else
     kv_scatter_kernel<float><<<g, 256, 0, s>>>((float *)a.qkv, a.ld, (float *)a.kbuf, (float *)a.vtbuf,
                                                a.rows_padded, a.n_heads, a.head_dim, a.row0, a.rows, a.rope, a.tok0,
-                                               a.grid_w, a.theta, nbk);
+                                               a.grid_w, a.theta, nbk, (const float *)a.q_norm_w, (const float *)a.k_norm_w,
+                                               a.norm_eps);
   return hipGetLastError();
 }
 

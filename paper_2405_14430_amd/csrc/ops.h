@@ -66,6 +66,8 @@ struct ScatterArgs {
   void *kbuf, *vtbuf;
   int rows_padded, n_heads, head_dim, row0, rows;
   int rope, tok0, grid_w; float theta;
+  const void *q_norm_w, *k_norm_w;   // [head_dim] scales of the per-head RMSNorm of q and k (before RoPE), or nullptr
+  float norm_eps;
 };
 hipError_t launch_kv_scatter(const ScatterArgs &a, hipStream_t s);
 

@@ -25,6 +25,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Derived {
   int n, T, Tj, Lkv, Lp, Tp, Rmax, mod_chunks, n_streams;
+  bool rope;      // q and k of the image rows are rotated (kind 3, or kind 2 with joint_rope)
   int B;          // images per call (classifier-free guidance runs the conditional and unconditional image together)
   size_t esz;
 };
@@ -52,7 +53,13 @@ const char *check_config(const pf_config *c, pf_status *st) {
   if (c->kind == PF_BLOCK_ADALN_ZERO && c->text_len != 0) return "kind 0 has no text";
   if (c->batch < 0 || c->batch > PF_MAX_BATCH) return "batch must be in [0, PF_MAX_BATCH] (0 means 1)";
   if (!(c->ln_eps > 0.f)) return "ln_eps must be > 0";
-  if (c->kind == PF_BLOCK_SINGLE_STREAM && !(c->rope_theta > 1.f)) return "rope_theta must be > 1";
+  if (c->joint_rope != 0 && c->joint_rope != 1) return "joint_rope must be 0 or 1";
+  if (c->joint_rope && c->kind != PF_BLOCK_MMDIT_JOINT) return "joint_rope applies to kind 2 only (kind 3 always rotates)";
+  const bool rope = c->kind == PF_BLOCK_SINGLE_STREAM || c->joint_rope;
+  if (rope && !(c->rope_theta > 1.f)) return "rope_theta must be > 1";
+  if (rope && c->head_dim % 4) return "RoPE needs head_dim to be a multiple of 4";
+  if (c->qk_norm != 0 && c->qk_norm != 1) return "qk_norm must be 0 or 1";
+  if (c->qk_norm && (c->head_dim & (c->head_dim - 1))) return "qk_norm needs a power-of-two head_dim";
   *st = PF_OK;
   return nullptr;
 }
@@ -70,6 +77,7 @@ Derived derive(const pf_config *c) {
   d.n_streams = c->kind == PF_BLOCK_MMDIT_JOINT ? 2 : 1;
   d.esz = dt_size(c->dtype);
   d.B = c->batch > 1 ? c->batch : 1;
+  d.rope = c->kind == PF_BLOCK_SINGLE_STREAM || c->joint_rope;
   return d;
 }
 
@@ -135,7 +143,7 @@ WsLayout ws_layout(const pf_config *c, const Derived &d) {
     w.xb = take(R * D * e);
     w.qc = take(R * D * e);
   }
-  if (c->kind == PF_BLOCK_SINGLE_STREAM) w.rope = take((size_t)d.Rmax * (size_t)(c->head_dim / 2) * 2 * sizeof(float));
+  if (d.rope) w.rope = take((size_t)d.Rmax * (size_t)(c->head_dim / 2) * 2 * sizeof(float));
   const int path = use_path(c);
   size_t ab = 0;
   // every query-row count a call can have: image-only patch, patch with the joint text rows, warm-up pass
@@ -276,19 +284,18 @@ hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const voi
 // through `rope_tab`, likewise); otherwise the projection lands in the qkv workspace and the scatter kernel moves (and
 // rotates) it, one launch per image and row range.
 pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, char *qs, int seg, char *kb, char *vb,
-                      int split, int row0a, int row0b, const void *rope_tab, int tok0) {
+                      int split, int row0a, int row0b, const void *rope_tab, int tok0, bool rope) {
   const pf_config &c = s->cfg;
   const Derived &d = s->d;
   const int D = c.hidden;
   const int rows = seg * d.B;
-  const bool rope = c.kind == PF_BLOCK_SINGLE_STREAM;
   GemmArgsKv kvr{kb, vb, d.Lp, c.head_dim, D, split, row0a, row0b, rope ? rope_tab : nullptr, d.B > 1 ? seg : 0,
                  (int64_t)s->img_elems()};
   GemmArgs probe{};
   probe.dt = c.dtype; probe.path = use_path(&c); probe.A = hs; probe.lda = D; probe.W = lw.w_qkv; probe.ldw = D;
   probe.bias = lw.b_qkv; probe.C = qs; probe.ldc = 3 * D; probe.M = rows; probe.N = 3 * D; probe.K = D; probe.epilogue = 0;
   probe.gelu_from = 3 * D; probe.kvr = kvr;
-  if (g_fuse_kv_route && gemm_kv_route_supported(probe)) {
+  if (g_fuse_kv_route && !c.qk_norm && gemm_kv_route_supported(probe)) {   // the fused route has no q / k RMSNorm
     PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, lw.w_qkv, D, lw.b_qkv, qs, 3 * D, rows, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0,
                 nullptr, 0, &kvr));
     return PF_OK;
@@ -301,10 +308,12 @@ pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, c
     char *kbb = kb + (size_t)b * s->img_elems() * d.esz, *vbb = vb + (size_t)b * s->img_elems() * d.esz;
     if (split > 0) {
       ScatterArgs sa{c.dtype, qb, 3 * D, kbb, vbb, d.Lp, c.n_heads, c.head_dim, row0a, split, rope ? 1 : 0, -1, c.grid_w, c.rope_theta};
+      if (c.qk_norm) { sa.q_norm_w = lw.q_norm_w; sa.k_norm_w = lw.k_norm_w; sa.norm_eps = c.ln_eps; }
       PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
     }
     ScatterArgs sb{c.dtype, qb + (size_t)split * 3 * D * d.esz, 3 * D, kbb, vbb, d.Lp, c.n_heads, c.head_dim, row0b, seg - split,
                    rope ? 1 : 0, tok0, c.grid_w, c.rope_theta};
+    if (c.qk_norm) { sb.q_norm_w = lw.q_norm_w; sb.k_norm_w = lw.k_norm_w; sb.norm_eps = c.ln_eps; }
     PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sb, st); }));
   }
   return PF_OK;
@@ -381,8 +390,12 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
   }
 
   const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
-  if (single)    // (cos, sin) of the RoPE angles of one image's rows, shared by all layers and images of the call
+  // (cos, sin) of the RoPE angles of one image's rows, shared by all layers and images of the call: [text; image] rows
+  // for the single-stream kind, the image rows alone for the two-stream kind (its text stream is not rotated)
+  if (single)
     PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_rope_table(ws + w.rope, R, Tt, img_off, c.grid_w, c.head_dim, c.rope_theta, st); }));
+  else if (d.rope)
+    PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_rope_table(ws + w.rope, n_img, 0, img_off, c.grid_w, c.head_dim, c.rope_theta, st); }));
   for (int l = 0; l < c.n_layers; ++l) {
     char *kb = s->kptr(l), *vb = s->vptr(l);
     if (single) {
@@ -391,7 +404,7 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       const int RT = B * R;
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xsrc, D, m, m + D, c.ln_eps, h, D, RT, D, 1, st, B > 1 ? R : 0, mstride); }));
       {
-        pf_status qs_ = qkv_project(s, h, lw, qkv, R, kb, vb, Tt, 0, row0_img, ws + w.rope, img_off);
+        pf_status qs_ = qkv_project(s, h, lw, qkv, R, kb, vb, Tt, 0, row0_img, ws + w.rope, img_off, true);
         if (qs_ != PF_OK) return qs_;
       }
       // MLP branch runs in parallel with attention: GELU(h W_up^T + b) lands right of the attention columns
@@ -415,7 +428,9 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       char *hs = h + sm.r0 * D * e;
       char *qs = qkv + sm.r0 * 3 * D * e;
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, B * sm.seg, D, 1, st, B > 1 ? sm.seg : 0, mstride); }));
-      pf_status qs_ = qkv_project(s, hs, *sm.lw, qs, sm.seg, kb, vb, 0, 0, sm.brow0, nullptr, -1);
+      const bool rot = d.rope && sm.lw == &s->img[l];   // image stream of a rotating two-stream block
+      pf_status qs_ = qkv_project(s, hs, *sm.lw, qs, sm.seg, kb, vb, 0, 0, sm.brow0, rot ? ws + w.rope : nullptr,
+                                  rot ? img_off : -1, rot);
       if (qs_ != PF_OK) return qs_;
     }
     if (B == 1) {
@@ -497,6 +512,7 @@ pf_status pf_stage_create(const pf_config *cfg, const pf_layer_weights *layers, 
       if (kind != PF_BLOCK_SINGLE_STREAM) ok = ok && lw->w_o && lw->b_o;
       if (kind == PF_BLOCK_ADALN_SINGLE_XATTN)
         ok = ok && lw->xattn_wq && lw->xattn_bq && lw->xattn_wkv && lw->xattn_bkv && lw->xattn_wo && lw->xattn_bo;
+      if (cfg->qk_norm) ok = ok && lw->q_norm_w && lw->k_norm_w;
       if (!ok) return fail(nullptr, PF_ERR_NULL, "a required weight pointer of layer " + std::to_string(l) + " is null");
     }
   }
@@ -689,7 +705,8 @@ pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void
 }
 
 pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *vtbuf, int rows_padded, int n_heads,
-                           int head_dim, int row0, int rows, int rope, int tok0, int grid_w, float rope_theta, void *stream) {
+                           int head_dim, int row0, int rows, int rope, int tok0, int grid_w, float rope_theta,
+                           const void *q_norm_w, const void *k_norm_w, float norm_eps, void *stream) {
   if (!qkv || !kbuf || !vtbuf) return PF_ERR_NULL;
   if (!dt_ok(dtype)) return PF_ERR_DTYPE;
   const int64_t d = (int64_t)n_heads * head_dim;
@@ -697,7 +714,10 @@ pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *v
       (int64_t)row0 + rows > rows_padded || rows_padded % 8 || !al16(qkv) || !al16(kbuf) || !al16(vtbuf))
     return PF_ERR_SHAPE;
   if (rope && (head_dim % 4 || grid_w < 1 || !(rope_theta > 1.f))) return PF_ERR_SHAPE;
+  if ((q_norm_w == nullptr) != (k_norm_w == nullptr)) return PF_ERR_NULL;
+  if (q_norm_w && ((head_dim & (head_dim - 1)) || !(norm_eps >= 0.f) || !al16(q_norm_w) || !al16(k_norm_w))) return PF_ERR_SHAPE;
   ScatterArgs sa{dtype, qkv, ld, kbuf, vtbuf, rows_padded, n_heads, head_dim, row0, rows, rope, tok0, grid_w, rope_theta};
+  sa.q_norm_w = q_norm_w; sa.k_norm_w = k_norm_w; sa.norm_eps = norm_eps;
   return launch_kv_scatter(sa, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 

@@ -40,6 +40,11 @@ def _rope_complex(t, grid_rc, H, theta):
     return torch.view_as_real(tc * rot[:, None, :]).reshape(n, d)
 
 
+def _qk_norm(t, w, H, eps):
+    n, d = t.shape
+    return Fn.rms_norm(t.view(n, H, d // H), (d // H,), weight=_t(w), eps=eps).reshape(n, d)
+
+
 def _mod(kind, w, cond):
     if kind == 1:
         return (_t(w["w_mod"]).reshape(-1) + cond).view(6, -1)
@@ -68,6 +73,8 @@ def full_forward(cfg, layers, x, cond, text=None):
             idx = torch.arange(L)
             rc = torch.cat([torch.zeros(T, 2, dtype=DT),
                             torch.stack([idx // cfg["grid_w"], idx % cfg["grid_w"]], 1).to(DT)], 0)
+            if cfg.get("qk_norm"):
+                q, k = _qk_norm(q, w["q_norm_w"], H, eps), _qk_norm(k, w["k_norm_w"], H, eps)
             q = _rope_complex(q, rc, H, cfg.get("rope_theta", 1e4))
             k = _rope_complex(k, rc, H, cfg.get("rope_theta", 1e4))
             a = _mha(q, k, v, H)
@@ -82,8 +89,19 @@ def full_forward(cfg, layers, x, cond, text=None):
         for (xs, ws), m in zip(streams, mods):
             h = ln(xs) * (1 + m[1]) + m[0]
             qkvs.append(Fn.linear(h, _t(ws["w_qkv"]), _t(ws["b_qkv"])))
+        if cfg.get("qk_norm"):
+            qkvs = [torch.cat([_qk_norm(t[:, :d], ws["q_norm_w"], H, eps), _qk_norm(t[:, d:2 * d], ws["k_norm_w"], H, eps),
+                               t[:, 2 * d:]], 1) for t, (_, ws) in zip(qkvs, streams)]
         qkv = torch.cat(qkvs, 0)
-        a_all = _mha(qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:], H)
+        qq, kk = qkv[:, :d], qkv[:, d:2 * d]
+        if kind == 2 and cfg.get("joint_rope"):
+            T = xt.shape[0]
+            idx = torch.arange(L)
+            rc = torch.cat([torch.zeros(T, 2, dtype=DT),
+                            torch.stack([idx // cfg["grid_w"], idx % cfg["grid_w"]], 1).to(DT)], 0)
+            qq = _rope_complex(qq.contiguous(), rc, H, cfg.get("rope_theta", 1e4))
+            kk = _rope_complex(kk.contiguous(), rc, H, cfg.get("rope_theta", 1e4))
+        a_all = _mha(qq, kk, qkv[:, 2 * d:], H)
         outs, r = [], 0
         for (xs, ws), m in zip(streams, mods):
             a = a_all[r:r + xs.shape[0]]

@@ -80,7 +80,7 @@ def test_batched_views_and_plan(lib):
     lib.pf_stage_destroy(h)
 
 
-BAD = [dict(hidden=100), dict(n_patches=7), dict(head_dim=12, n_heads=32), dict(dtype_code=5), dict(kind=9),
+BAD = [dict(qk_norm=2), dict(joint_rope=1), dict(qk_norm=1, head_dim=48, n_heads=8), dict(hidden=100), dict(n_patches=7), dict(head_dim=12, n_heads=32), dict(dtype_code=5), dict(kind=9),
        dict(grid_w=3), dict(mlp_dim=100), dict(n_layers=0), dict(ln_eps=0.0)]
 
 
@@ -167,7 +167,9 @@ def test_op_argument_checks_without_launching(lib):
     assert lib.pf_op_gemm(7, 0, p, 24, p, 24, None, p, 64, 4, 64, 24, 0, 64, 1, None, None, 0, None, 0, None) == -4
     assert lib.pf_op_attention(1, 0, p, 64, p, p, 0, 128, 1, 64, p, 64, 4, 1, None, 0, None) == -3      # no key rows
     assert lib.pf_op_attention(1, 0, p, 64, p, p, 100, 128, 1, 64, p, 64, 4, 2, None, 0, None) == -7    # no workspace
-    assert lib.pf_op_kv_scatter(1, p, 192, p, p, 128, 1, 64, 100, 64, 0, -1, 1, 1e4, None) == -3        # rows overflow
+    assert lib.pf_op_kv_scatter(1, p, 192, p, p, 128, 1, 64, 100, 64, 0, -1, 1, 1e4, None, None, 0.0, None) == -3   # rows overflow
+    assert lib.pf_op_kv_scatter(1, p, 192, p, p, 128, 1, 64, 0, 64, 0, -1, 1, 1e4, p, None, 1e-6, None) == -1      # one norm weight only
+    assert lib.pf_op_kv_scatter(1, p, 3 * 72, p, p, 128, 1, 72, 0, 64, 0, -1, 1, 1e4, p, p, 1e-6, None) == -3      # head_dim not a power of two
     assert lib.pf_op_ln_modulate(0, p, 12, p, p, 1e-6, p, 12, 4, 12, 1, None) == -3
 
 

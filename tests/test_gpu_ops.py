@@ -229,6 +229,35 @@ def test_kv_scatter_rope(dtype):
     assert torch.equal(qkv2, _dev(qkv_np, dtype))
 
 
+@pytest.mark.parametrize("dtype", [F32, BF])
+@pytest.mark.parametrize("H,dh,rope", [(3, 64, False), (2, 128, True), (5, 32, True)])
+def test_kv_scatter_qk_rmsnorm(dtype, H, dh, rope):
+    """q and k are RMS-normalised per head (then rotated) in place; K in the buffer is exactly what qkv then holds."""
+    rows, row0, Lp, gw, tok0 = 77, 24, 128, 13, 5
+    d = H * dh
+    rng = _rng(123 + dh)
+    qkv_np = _draw(rng, (rows, 3 * d), dtype, 3.0)
+    wq, wk = _draw(rng, (dh,), dtype) * 0.25 + 1.0, _draw(rng, (dh,), dtype) * 0.25 + 1.0
+    wq, wk = wl.round_to_bf16(wq) if dtype == BF else wq, wl.round_to_bf16(wk) if dtype == BF else wk
+    qkv = _dev(qkv_np, dtype)
+    K = torch.zeros(H, Lp, dh, dtype=dtype, device="cuda")
+    Vt = torch.zeros(H, dh, Lp, dtype=dtype, device="cuda")
+    _pkg().pf_op_kv_scatter(qkv, K, Vt, Lp, H, dh, row0, rope=rope, tok0=tok0, grid_w=gw, theta=1e4,
+                            q_norm_w=_dev(wq, dtype), k_norm_w=_dev(wk, dtype), norm_eps=1e-6)
+    torch.cuda.synchronize()
+    qn = po.rms_norm_heads(qkv_np[:, :d], wq, H, 1e-6)
+    kn = po.rms_norm_heads(qkv_np[:, d:2 * d], wk, H, 1e-6)
+    if rope:
+        toks = np.arange(tok0, tok0 + rows)
+        ang = po.rope_angles(toks // gw, toks % gw, dh, 1e-4 * 0 + 1e4)
+        qn, kn = po.rope_apply(qn, ang, H), po.rope_apply(kn, ang, H)
+    assert _close(qkv[:, :d], qn, dtype, 1e-4) and _close(qkv[:, d:2 * d], kn, dtype, 1e-4)
+    assert torch.equal(qkv[:, 2 * d:], _dev(qkv_np[:, 2 * d:], dtype))
+    assert torch.equal(K[:, row0:row0 + rows], qkv[:, d:2 * d].reshape(rows, H, dh).transpose(0, 1))
+    assert torch.equal(Vt[:, :, row0:row0 + rows], qkv[:, 2 * d:].reshape(rows, H, dh).permute(1, 2, 0))
+    assert not bool(K[:, :row0].any()) and not bool(K[:, row0 + rows:].any())
+
+
 ATTN_CASES = [  # H, dh, nq, Lkv, splits, gain
     (2, 64, 70, 333, 1, 1.0), (3, 72, 200, 1000, 3, 1.0), (2, 128, 130, 515, 2, 1.0), (2, 40, 33, 120, 1, 1.0),
     (2, 72, 129, 4096, 4, 8.0), (1, 128, 64, 700, 5, 8.0), (4, 64, 256, 64, 1, 1.0), (2, 96, 31, 257, 1, 1.0),

@@ -53,7 +53,7 @@ def test_axpy_matches_update_rule():
 
 
 @pytest.mark.parametrize("name,N,S", [("K0f", 2, 3), ("K1f", 2, 3), ("K2f", 2, 3), ("K3f", 2, 3), ("K0f", 3, 2),
-                                      ("C2s", 2, 3), ("C3s", 2, 3), ("C4s", 2, 2)])
+                                      ("C2s", 2, 3), ("C3s", 2, 3), ("C4s", 2, 2), ("K2n", 2, 2), ("C4n", 2, 2)])
 def test_sampling_loop_matches_oracle(name, N, S):
     from paper_2405_14430_amd.pipeline import Pipeline
     cfg = wl.CONFIGS[name]

@@ -15,7 +15,7 @@ import workloads as wl
 from oracle import pf_oracle as po
 from full_forward_ref import full_forward
 
-FP32_TWINS = ["K0f", "K1f", "K2f", "K3f"]
+FP32_TWINS = ["K0f", "K1f", "K2f", "K3f", "K2n", "K3n"]   # K2n / K3n: q,k RMSNorm (and RoPE on the two-stream block)
 RTOL = 1e-9
 
 
@@ -268,6 +268,40 @@ def test_rope_norm_relative_position_and_complex_form():
 
 
 # ---- I9 / I10 / I6 / I7 -------------------------------------------------------------------------
+def test_qk_rmsnorm_identities_and_library():
+    """RMSNorm per head: unit weights give unit rms per (row, head); the output does not depend on the scale of the
+    input; torch's rms_norm agrees; a head-wise permutation of rows commutes with it."""
+    rng = np.random.default_rng(3)
+    n, H, dh = 7, 3, 64
+    t = rng.normal(size=(n, H * dh)) * rng.uniform(0.1, 9.0, size=(n, 1))
+    w = 1.0 + 0.3 * rng.normal(size=dh)
+    unit = po.rms_norm_heads(t, np.ones(dh), H, 0.0).reshape(n, H, dh)
+    assert np.allclose(np.sqrt(np.mean(unit ** 2, axis=-1)), 1.0, atol=1e-12)
+    a, b = po.rms_norm_heads(t, w, H, 0.0), po.rms_norm_heads(37.5 * t, w, H, 0.0)
+    assert np.allclose(a, b, rtol=1e-12, atol=1e-12)
+    ref = torch.nn.functional.rms_norm(torch.as_tensor(t).view(n, H, dh), (dh,), weight=torch.as_tensor(w), eps=1e-6)
+    assert np.allclose(po.rms_norm_heads(t, w, H, 1e-6), ref.reshape(n, H * dh).numpy(), rtol=1e-12, atol=1e-12)
+    # a zero row stays finite with eps > 0
+    z = po.rms_norm_heads(np.zeros((2, H * dh)), w, H, 1e-6)
+    assert np.all(z == 0.0)
+
+
+def test_qk_norm_changes_the_result_and_bounds_the_scores():
+    """The flag is live: switching it off changes the output; with it on, every attention score is bounded by
+    dh * max|wq| * max|wk| / sqrt(dh) (Cauchy-Schwarz on unit-rms vectors), whatever the gain of the projection."""
+    cfg = wl.variant(wl.CONFIGS["K3n"], qk_gain=16.0)
+    W, A = wl.make_weights(cfg), wl.make_activations(cfg)
+    o = po.StageOracle(cfg, W)
+    warm, _ = o.kv_init(A["x"], A["cond"], text=A["text"])
+    off = po.StageOracle(dict(cfg, qk_norm=0), W)
+    warm_off, _ = off.kv_init(A["x"], A["cond"], text=A["text"])
+    assert _rel(warm, warm_off) > 1e-3
+    H, dh = cfg["n_heads"], cfg["head_dim"]
+    K = o.kbuf[0].reshape(-1, H, dh)
+    bound = np.sqrt(dh) * np.max(np.abs(W[0]["k_norm_w"]))
+    assert np.all(np.sqrt(np.sum(K * K, axis=-1)) <= bound * (1 + 1e-9))     # |k_h| <= sqrt(dh) * max|w| (RoPE keeps norms)
+
+
 def test_zero_gates_make_the_stage_identity_but_still_write_kv():
     cfg, W, A = _setup("K0f")
     d = cfg["hidden"]

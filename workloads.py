@@ -21,7 +21,7 @@ KIND_MMDIT_JOINT = 2         # SD3: two weight streams, one joint attention
 KIND_SINGLE_STREAM = 3       # Flux single-stream: parallel attn+MLP, 2-D RoPE
 
 _BASE = dict(text_len=0, cross_dim=0, ln_eps=1e-6, rope_theta=1e4, gelu_tanh=1,
-             w_std=0.02, qk_gain=1.0, cond_std=None)
+             w_std=0.02, qk_gain=1.0, cond_std=None, qk_norm=0, joint_rope=0)
 
 
 def _cfg(**kw):
@@ -70,6 +70,18 @@ CONFIGS = {
                 seq_img=198, grid_h=11, grid_w=18, n_patches=3, text_len=29, w_std="fan_in", seed=22),
     "K3f": _cfg(kind=3, dtype="f32", n_layers=2, hidden=256, n_heads=2, head_dim=128, mlp_dim=640,
                 seq_img=204, grid_h=12, grid_w=17, n_patches=3, text_len=21, w_std="fan_in", seed=23),
+    # q / k RMSNorm (and RoPE on the two-stream joint block): the attention front end of the Flux-family blocks
+    "K2n": _cfg(kind=2, dtype="f32", n_layers=2, hidden=128, n_heads=2, head_dim=64, mlp_dim=320,
+                seq_img=198, grid_h=11, grid_w=18, n_patches=3, text_len=29, w_std="fan_in", seed=24,
+                qk_norm=1, joint_rope=1),
+    "K3n": _cfg(kind=3, dtype="f32", n_layers=2, hidden=256, n_heads=2, head_dim=128, mlp_dim=640,
+                seq_img=204, grid_h=12, grid_w=17, n_patches=3, text_len=21, w_std="fan_in", seed=25, qk_norm=1),
+    "C3n": _cfg(kind=2, dtype="bf16", n_layers=2, hidden=256, n_heads=4, head_dim=64, mlp_dim=1024,
+                seq_img=1080, grid_h=30, grid_w=36, n_patches=4, text_len=77, seed=26, qk_norm=1, joint_rope=1),
+    "C4n": _cfg(kind=3, dtype="bf16", n_layers=2, hidden=384, n_heads=3, head_dim=128, mlp_dim=1536,
+                seq_img=1500, grid_h=30, grid_w=50, n_patches=5, text_len=45, seed=27, qk_norm=1),
+    "C3r": _cfg(kind=2, dtype="bf16", n_layers=2, hidden=256, n_heads=4, head_dim=64, mlp_dim=1024,
+                seq_img=1080, grid_h=30, grid_w=36, n_patches=4, text_len=77, seed=28, joint_rope=1),
 }
 
 
@@ -142,6 +154,9 @@ def _stream_weights(cfg, rng):
         w["xattn_wq"], w["xattn_bq"] = _linear(cfg, rng, d, d)
         w["xattn_wkv"], w["xattn_bkv"] = _linear(cfg, rng, 2 * d, cfg["cross_dim"])
         w["xattn_wo"], w["xattn_bo"] = _linear(cfg, rng, d, d)
+    if cfg.get("qk_norm"):   # learned per-channel scales of the q / k RMSNorm, shared by the heads (drawn last)
+        w["q_norm_w"] = _store(cfg, 1.0 + 0.25 * _normal(rng, (cfg["head_dim"],)))
+        w["k_norm_w"] = _store(cfg, 1.0 + 0.25 * _normal(rng, (cfg["head_dim"],)))
     return w
 
 
