@@ -54,6 +54,10 @@ struct Cfg {
   static constexpr int STAGE = K_BYTES + V_BYTES;
   static constexpr int LK = (K_INSTR + 3) / 4, LV = (V_INSTR + 3) / 4;   // instructions per wave
   static constexpr int LPS = LK + LV;
+  // Head sizes that leave padding rows in the V^T tile (72 -> 96 rows) get the softmax denominator for free: padding
+  // row DH holds ones, so row DH of O^T accumulates sum_j P[j][q] in the matrix pipe (with the same rescaling as the
+  // numerator) and the per-element additions of the running sum disappear from the VALU stream.
+  static constexpr bool ONES_ROW = V_ROWS > DH;
   // swizzle key of K row r (applied to the chunk index)
   static __device__ __forceinline__ int kkey(int r) {
     return DH == 64 ? ((r >> 1) & 7) : (DH == 128 ? (r & 15) : 0);
@@ -90,7 +94,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
     constexpr int PADB = (C::V_ROWS - DH) * 128;
     for (int e = tid; e < NS * PADB / 16; e += 256) {
       int st = e / (PADB / 16), o = e % (PADB / 16);
-      *reinterpret_cast<uint4 *>(smem + st * C::STAGE + C::K_BYTES + DH * 128 + o * 16) = make_uint4(0, 0, 0, 0);
+      const unsigned fill = (C::ONES_ROW && o < 8) ? 0x3F803F80u : 0u;   // first padding row: bf16 1.0 in every key column
+      *reinterpret_cast<uint4 *>(smem + st * C::STAGE + C::K_BYTES + DH * 128 + o * 16) = make_uint4(fill, fill, fill, fill);
     }
   }
 
@@ -231,12 +236,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
       for (int r = 0; r < 16; r += 2) {
         float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], sl2, mneg));
         float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r + 1], sl2, mneg));
-        psum += p0 + p1;
+        if constexpr (!C::ONES_ROW) psum += p0 + p1;
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
         pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
       }
-    l_run = l_run * alpha + psum;
+    if constexpr (!C::ONES_ROW) l_run = l_run * alpha + psum;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // skip the rescale when no lane's maximum moved
 #pragma unroll
       for (int cb = 0; cb < C::CB; ++cb)
@@ -276,7 +281,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   wait_vmcnt<0>();
 
   // ---- finish
-  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  // O^T row DH sits in block DH / 32 at local row DH % 32 = 8 * (r / 4) + 4 * hi + r % 4: for DH = 72 that is register 4
+  // of the lanes with hi = 0, i.e. lane l32 holds the sum of query l32
+  static_assert(!C::ONES_ROW || (DH % 32) == 8, "register index of the ones row is worked out for DH % 32 == 8");
+  const float l_tot = C::ONES_ROW ? __shfl(oacc[C::CB - 1][4], l32, kWave) : l_run + __shfl_xor(l_run, 32, kWave);
   const int qi = q0 + l32;
   if (qi >= nq) return;
   const int d = H * DH;
