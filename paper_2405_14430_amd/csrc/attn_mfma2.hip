@@ -22,6 +22,8 @@
 
 namespace pf {
 
+int g_attn_stages = 0;   // tuning hook: 0 = default ring depth, 2 / 3 = forced
+
 namespace {
 
 constexpr int TQ = 128;
@@ -64,7 +66,11 @@ struct Cfg {
   }
 };
 
-template <int DH, int NS>
+// PRE: the queries arrive already multiplied by log2(e) / sqrt(dh) (the producer folds the factor into its fp32
+// epilogue, so q is rounded to bf16 once either way; scaling bf16 queries here would round them a second time and
+// costs accuracy on peaked softmaxes).  The score MFMAs then deliver exponents of 2 and the softmax of an element
+// needs no multiply-add.
+template <int DH, int NS, bool PRE>
 __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__restrict__ q, int64_t ldq,
                                                             const bf16_t *__restrict__ kbuf,
                                                             const bf16_t *__restrict__ vtbuf, int kv_rows, int Lp, int H,
@@ -163,6 +169,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
     for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;   // running maximum of the raw scores; per-lane partial sum
   const float sl2 = kLog2e / sqrtf((float)DH);
+  // PRE: probabilities are taken relative to a reference exponent m_ref per query that only moves when a tile's
+  // maximum exceeds it by more than kSlack (and on the first tile): p = 2^(s - m_ref) <= 2^kSlack.  -m_ref is kept
+  // in a 16-register block that seeds the score accumulators (the C operand of a tile's first MFMA), so the
+  // subtraction costs no VALU instruction: the softmax of an element is max, exp2, convert.
+  constexpr float kSlack = 8.f;
+  float m_ref = 0.f;
+  f32x16 cneg;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) cneg[r] = 0.f;
 
   // fragment addressing, loop invariant: address = row base + ((chunk ^ key) << 4); the chunk's low bit is the
   // half-wave index, so it is folded into the per-lane key and the rest of the chunk index is a compile-time XOR mask
@@ -201,7 +216,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
 #pragma unroll
       for (int ks = 0; ks < C::KS16; ++ks) {
         bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + krow_off[b] + (kx[b] ^ (ks << 5)));
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[b], 0, 0, 0);
+        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], (PRE && ks == 0) ? cneg : sacc[b], 0, 0, 0);
       }
       if constexpr (C::TAIL8) {
         bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(st + krow_off[b] + C::KS16 * 32 + hi * 8);
@@ -223,30 +238,64 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[b][r]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
-    const float mneg = -m_new * sl2;
-    m_run = m_new;
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));     // both lanes of a query agree
     float psum = 0.f;
     unsigned pk[2][8];   // packed bf16 pairs (r, r+1) of the softmax weights
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    if constexpr (PRE) {
+      const bool first = t == t_begin;
+      if (first || __builtin_amdgcn_ballot_w64(tmax > kSlack) != 0) {
+        // move the reference: to the tile maximum on the first tile, up by the excess later on
+        const float delta = first ? tmax : fmaxf(tmax, 0.f);
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], sl2, mneg));
-        float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r + 1], sl2, mneg));
-        if constexpr (!C::ONES_ROW) psum += p0 + p1;
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
-        pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
+          for (int r = 0; r < 16; ++r) sacc[b][r] -= delta;
+        if (!first) {
+          const float alpha = __builtin_amdgcn_exp2f(-delta);
+          l_run *= alpha;
+#pragma unroll
+          for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+        }
+        m_ref += delta;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cneg[r] = -m_ref;
       }
-    if constexpr (!C::ONES_ROW) l_run = l_run * alpha + psum;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // skip the rescale when no lane's maximum moved
 #pragma unroll
-      for (int cb = 0; cb < C::CB; ++cb)
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+        for (int r = 0; r < 16; r += 2) {
+          float p0 = __builtin_amdgcn_exp2f(sacc[b][r]);
+          float p1 = __builtin_amdgcn_exp2f(sacc[b][r + 1]);
+          if constexpr (!C::ONES_ROW) psum += p0 + p1;
+          bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
+          pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
+        }
+      if constexpr (!C::ONES_ROW) l_run += psum;
+    } else {
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
+      const float mneg = -m_new * sl2;
+      m_run = m_new;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r], sl2, mneg));
+          float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[b][r + 1], sl2, mneg));
+          if constexpr (!C::ONES_ROW) psum += p0 + p1;
+          bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
+          pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
+        }
+      if constexpr (!C::ONES_ROW) l_run = l_run * alpha + psum;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // skip the rescale when no lane's maximum moved
+#pragma unroll
+        for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+      }
     }
     // ---- O^T += V^T . P^T.  For each K=16 step the half-waves trade registers so that lane-half `hi` holds the
     // weights of kv rows 16*step + 8*hi .. +7 (in order); V^T supplies the same rows with one 16-byte read.
@@ -316,19 +365,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
       }
     if (hi == 0) {
       float *ml = ws + (size_t)splits * nq * d + (((size_t)sp * nq + qi) * H + h) * 2;
-      ml[0] = m_run * sl2 * kLn2;   // natural-log domain maximum of the scaled scores, for the combine kernel
+      ml[0] = (PRE ? m_ref : m_run * sl2) * kLn2;   // natural-log domain reference of the scaled scores, for the combine kernel
       ml[1] = l_tot;
     }
   }
 }
 
-template <int DH, int NS>
+template <int DH, int NS, bool PRE = false>
 hipError_t launch2(const AttnArgs &a, hipStream_t s) {
   using C = Cfg<DH>;
   constexpr int smem = NS * C::STAGE;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH, NS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH, NS, PRE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -336,7 +385,7 @@ hipError_t launch2(const AttnArgs &a, hipStream_t s) {
   const int qtiles = (a.nq + TQ - 1) / TQ;
   const int B = a.batch > 1 ? a.batch : 1;
   dim3 g(qtiles * a.n_heads * B * a.splits);
-  attn_mfma2_kernel<DH, NS><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
+  attn_mfma2_kernel<DH, NS, PRE><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
                                              a.kv_rows, a.rows_padded, a.n_heads * B, (bf16_t *)a.out, a.ldo, a.nq, a.splits,
                                              qtiles, a.ws, a.n_heads);
   return hipGetLastError();
@@ -344,17 +393,26 @@ hipError_t launch2(const AttnArgs &a, hipStream_t s) {
 
 }  // namespace
 
+bool attn_mfma2_takes_prescaled_q(int head_dim) {
+  return (head_dim == 64 || head_dim == 72 || head_dim == 128) && (g_attn_stages == 0 || g_attn_stages == 2);
+}
+
 bool attn_mfma2_supported(const AttnArgs &a) {
   return (a.head_dim == 64 || a.head_dim == 72 || a.head_dim == 128) && a.rows_padded % TK == 0;
 }
 
-int g_attn_stages = 0;   // tuning hook: 0 = default ring depth, 2 / 3 = forced
 
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s) {
   if (a.nq <= 0) return hipSuccess;
   // Two stages by default: in-stage A/B runs on MI355X showed no gain from a third stage for dh = 64 / 72 (1626 vs
   // 1635 us on the 64K-key PixArt stage) and a loss for dh = 128, where it halves the workgroups per CU (430 vs 565 us).
   const int ns = g_attn_stages ? g_attn_stages : 2;
+  if (a.q_prescaled && ns != 2) return hipErrorInvalidValue;   // only the two-stage kernels have the variant
+  if (a.q_prescaled) {
+    if (a.head_dim == 64) return launch2<64, 2, true>(a, s);
+    if (a.head_dim == 72) return launch2<72, 2, true>(a, s);
+    return launch2<128, 2, true>(a, s);
+  }
   if (a.head_dim == 64) return ns == 3 ? launch2<64, 3>(a, s) : launch2<64, 2>(a, s);
   if (a.head_dim == 72) return ns == 3 ? launch2<72, 3>(a, s) : launch2<72, 2>(a, s);
   return ns == 3 ? launch2<128, 3>(a, s) : launch2<128, 2>(a, s);

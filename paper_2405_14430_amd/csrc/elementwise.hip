@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(T *__restrict__ qkv, in
                                                          T *__restrict__ vtbuf, int Lp, int H, int dh, int row0,
                                                          int rows, int rope, int tok0, int grid_w, float theta,
                                                          int nbk, const T *__restrict__ q_norm_w,
-                                                         const T *__restrict__ k_norm_w, float norm_eps) {
+                                                         const T *__restrict__ k_norm_w, float norm_eps, float q_scale) {
   constexpr int V = Vec16<T>::N;
   const int d = H * dh;
   const bool norm = q_norm_w != nullptr;
@@ -245,6 +245,10 @@ __global__ __launch_bounds__(256) void kv_scatter_kernel(T *__restrict__ qkv, in
       }
     }
     if (inplace) {
+      if (part == 0 && q_scale != 0.f) {
+#pragma unroll
+        for (int t = 0; t < V; ++t) v[t] *= q_scale;
+      }
       Vec16<T>::store(src, v);   // normalised / rotated (or, for text rows without norm, unchanged) values stay in qkv
       Vec16<T>::load(src, v);    // what reaches the buffer is exactly what qkv now holds
     }
@@ -290,12 +294,12 @@ hipError_t launch_kv_scatter(const ScatterArgs &a, hipStream_t s) {
     kv_scatter_kernel<bf16_t><<<g, 256, 0, s>>>((bf16_t *)a.qkv, a.ld, (bf16_t *)a.kbuf, (bf16_t *)a.vtbuf,
                                                 a.rows_padded, a.n_heads, a.head_dim, a.row0, a.rows, a.rope,
                                                 a.tok0, a.grid_w, a.theta, nbk, (const bf16_t *)a.q_norm_w,
-                                                (const bf16_t *)a.k_norm_w, a.norm_eps);
+                                                (const bf16_t *)a.k_norm_w, a.norm_eps, a.q_scale);
   else
     kv_scatter_kernel<float><<<g, 256, 0, s>>>((float *)a.qkv, a.ld, (float *)a.kbuf, (float *)a.vtbuf,
                                                a.rows_padded, a.n_heads, a.head_dim, a.row0, a.rows, a.rope, a.tok0,
                                                a.grid_w, a.theta, nbk, (const float *)a.q_norm_w, (const float *)a.k_norm_w,
-                                               a.norm_eps);
+                                               a.norm_eps, a.q_scale);
   return hipGetLastError();
 }
 

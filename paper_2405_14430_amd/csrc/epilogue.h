@@ -19,6 +19,7 @@ struct KvRoute {
   const float2 *rope;          // [rows of one image][dh/2] (cos, sin) per GEMM row, or nullptr
   int seg;                     // > 0: GEMM rows are image-major, seg rows per image; mapping applies inside the image
   int64_t img_stride;          // elements between consecutive images' K (and V^T) buffers
+  float q_scale;               // != 0: q columns are multiplied by it (the attention kernel's log2(e) / sqrt(dh))
 };
 
 template <typename T>
@@ -54,7 +55,7 @@ template <typename T, typename Args>
 inline Epilogue<T> make_epilogue(const Args &a) {
   Epilogue<T> e;
   e.kv = KvRoute{a.kvr.kbuf, a.kvr.vtbuf, a.kvr.Lp, a.kvr.dh, a.kvr.d, a.kvr.split, a.kvr.row0a, a.kvr.row0b,
-                 (const float2 *)a.kvr.rope, a.kvr.seg, a.kvr.img_stride};
+                 (const float2 *)a.kvr.rope, a.kvr.seg, a.kvr.img_stride, a.kvr.q_scale};
   e.bias = (const T *)a.bias; e.C = a.C; e.ldc = a.ldc; e.mode = a.epilogue; e.gelu_from = a.gelu_from;
   e.gelu_tanh = a.gelu_tanh; e.gate = a.gate; e.gate_seg = a.gate_seg; e.gate_stride = a.gate_stride; e.R = a.R; e.ldr = a.ldr; e.C2 = (T *)a.C2; e.ldc2 = a.ldc2;
   return e;

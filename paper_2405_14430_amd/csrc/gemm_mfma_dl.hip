@@ -101,6 +101,10 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
           v[e + 1] = a0 * cs.y + b0 * cs.x;
         }
       }
+      if (part == 0 && kv.q_scale != 0.f) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= kv.q_scale;
+      }
       bf16x8 o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];

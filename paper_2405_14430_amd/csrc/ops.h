@@ -36,7 +36,8 @@ hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *
 struct KvRoute;   // epilogue.h
 // seg > 0: GEMM rows are image-major, seg per image; image b writes into kbuf / vtbuf + b * img_stride elements and
 // the row mapping (split, row0a, row0b, rope row) applies to the row index inside the image.
-struct GemmArgsKv { void *kbuf, *vtbuf; int Lp, dh, d, split, row0a, row0b; const void *rope; int seg; int64_t img_stride; };
+struct GemmArgsKv { void *kbuf, *vtbuf; int Lp, dh, d, split, row0a, row0b; const void *rope; int seg; int64_t img_stride;
+                    float q_scale; };   // q_scale != 0: the q columns are multiplied by it before they are rounded
 
 struct GemmArgs {
   int dt, path;
@@ -68,6 +69,7 @@ struct ScatterArgs {
   int rope, tok0, grid_w; float theta;
   const void *q_norm_w, *k_norm_w;   // [head_dim] scales of the per-head RMSNorm of q and k (before RoPE), or nullptr
   float norm_eps;
+  float q_scale;                     // != 0 (needs rope or norm: q is rewritten anyway): q is multiplied by it
 };
 hipError_t launch_kv_scatter(const ScatterArgs &a, hipStream_t s);
 
@@ -79,6 +81,7 @@ struct AttnArgs {
   void *out; int64_t ldo;
   int nq, splits;
   float *ws;           // partial results when splits > 1
+  int q_prescaled;     // q already carries the factor log2(e) / sqrt(head_dim) (bf16 direct-to-LDS kernel only)
   int batch;           // images per call (0 or 1: one).  q / out hold batch x nq rows, image-major; kbuf / vtbuf hold
                        // batch x n_heads heads, image-major; the workspace is sized for n_heads * batch heads
 };
@@ -98,6 +101,7 @@ hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
 bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS variant for head sizes 64 / 72 / 128
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s);
+bool attn_mfma2_takes_prescaled_q(int head_dim);           // its kernel for this head size has a prescaled-q variant
 hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s);   // picks between the two
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);
 

@@ -15,6 +15,8 @@
 using namespace pf;
 
 static int g_fuse_kv_route = 1;   // tuning hook 200/201: K/V written by the QKV GEMM epilogue (1) or the scatter kernel (0)
+static int g_fold_q_scale = 1;    // tuning hook 800/801: q handed to the attention kernel with its exponent factor folded in
+namespace pf { extern int g_attn_variant; }
 
 namespace {
 
@@ -264,12 +266,13 @@ int plan_splits(const pf_stage *s, int nq, int kv_rows) {
 }
 
 hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const void *kb, const void *vb, int kv_rows,
-                     int rows_padded, void *out, int64_t ldo, int nq) {
+                     int rows_padded, void *out, int64_t ldo, int nq, bool q_prescaled = false) {
   AttnArgs a{};
   a.dt = s->cfg.dtype; a.path = use_path(&s->cfg);
   a.q = q; a.ldq = ldq; a.kbuf = kb; a.vtbuf = vb; a.kv_rows = kv_rows; a.rows_padded = rows_padded;
   a.n_heads = s->cfg.n_heads; a.head_dim = s->cfg.head_dim; a.out = out; a.ldo = ldo; a.nq = nq;
   a.batch = s->d.B;
+  a.q_prescaled = q_prescaled ? 1 : 0;
   a.splits = plan_splits(s, nq, kv_rows);
   a.ws = (float *)(s->ws + s->w.attn);
   hipError_t e = run(s, cls, [&] { return a.path == PATH_SIMT ? launch_attn_simt(a, s->stream) : launch_attn_bf16(a, s->stream); });
@@ -283,19 +286,32 @@ hipError_t attention(pf_stage *s, int cls, const void *q, int64_t ldq, const voi
 // the bf16 GEMM's vectorised epilogue can do it, k and v go straight from the accumulators into K / V^T (q, and RoPE
 // through `rope_tab`, likewise); otherwise the projection lands in the qkv workspace and the scatter kernel moves (and
 // rotates) it, one launch per image and row range.
+// How the QKV projection of a stream reaches the buffers: through the GEMM epilogue, or through the scatter kernel,
+// which rewrites q in fp32 only when it normalises or rotates.
+enum { ROUTE_FUSED = 0, ROUTE_SCATTER_REWRITE, ROUTE_SCATTER_PLAIN };
+int qkv_route(const pf_stage *s, const void *hs, const pf_layer_weights &lw, const char *qs, bool rope) {
+  const pf_config &c = s->cfg;
+  const int D = c.hidden;
+  GemmArgs probe{};
+  probe.dt = c.dtype; probe.path = use_path(&c); probe.A = hs; probe.lda = D; probe.W = lw.w_qkv; probe.ldw = D;
+  probe.bias = lw.b_qkv; probe.C = (void *)qs; probe.ldc = 3 * D; probe.M = 1; probe.N = 3 * D; probe.K = D; probe.epilogue = 0;
+  probe.gelu_from = 3 * D;
+  probe.kvr = GemmArgsKv{(void *)qs, (void *)qs, s->d.Lp, c.head_dim, D, 0, 0, 0, nullptr, 0, 0, 0.f};
+  if (g_fuse_kv_route && !c.qk_norm && gemm_kv_route_supported(probe)) return ROUTE_FUSED;   // the fused route has no q / k RMSNorm
+  return (rope || c.qk_norm) ? ROUTE_SCATTER_REWRITE : ROUTE_SCATTER_PLAIN;
+}
+
+// q_scale != 0: q is to leave this function multiplied by it (folded into whichever fp32 step writes q; the caller only
+// asks for it when every q row of the coming attention launch goes through such a step).
 pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, char *qs, int seg, char *kb, char *vb,
-                      int split, int row0a, int row0b, const void *rope_tab, int tok0, bool rope) {
+                      int split, int row0a, int row0b, const void *rope_tab, int tok0, bool rope, float q_scale) {
   const pf_config &c = s->cfg;
   const Derived &d = s->d;
   const int D = c.hidden;
   const int rows = seg * d.B;
   GemmArgsKv kvr{kb, vb, d.Lp, c.head_dim, D, split, row0a, row0b, rope ? rope_tab : nullptr, d.B > 1 ? seg : 0,
-                 (int64_t)s->img_elems()};
-  GemmArgs probe{};
-  probe.dt = c.dtype; probe.path = use_path(&c); probe.A = hs; probe.lda = D; probe.W = lw.w_qkv; probe.ldw = D;
-  probe.bias = lw.b_qkv; probe.C = qs; probe.ldc = 3 * D; probe.M = rows; probe.N = 3 * D; probe.K = D; probe.epilogue = 0;
-  probe.gelu_from = 3 * D; probe.kvr = kvr;
-  if (g_fuse_kv_route && !c.qk_norm && gemm_kv_route_supported(probe)) {   // the fused route has no q / k RMSNorm
+                 (int64_t)s->img_elems(), q_scale};
+  if (qkv_route(s, hs, lw, qs, rope) == ROUTE_FUSED) {
     PF_TRY(gemm(s, PF_KC_GEMM_QKV, hs, D, lw.w_qkv, D, lw.b_qkv, qs, 3 * D, rows, 3 * D, D, 0, 3 * D, nullptr, nullptr, 0,
                 nullptr, 0, &kvr));
     return PF_OK;
@@ -309,11 +325,13 @@ pf_status qkv_project(pf_stage *s, const void *hs, const pf_layer_weights &lw, c
     if (split > 0) {
       ScatterArgs sa{c.dtype, qb, 3 * D, kbb, vbb, d.Lp, c.n_heads, c.head_dim, row0a, split, rope ? 1 : 0, -1, c.grid_w, c.rope_theta};
       if (c.qk_norm) { sa.q_norm_w = lw.q_norm_w; sa.k_norm_w = lw.k_norm_w; sa.norm_eps = c.ln_eps; }
+      sa.q_scale = q_scale;
       PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sa, st); }));
     }
     ScatterArgs sb{c.dtype, qb + (size_t)split * 3 * D * d.esz, 3 * D, kbb, vbb, d.Lp, c.n_heads, c.head_dim, row0b, seg - split,
                    rope ? 1 : 0, tok0, c.grid_w, c.rope_theta};
     if (c.qk_norm) { sb.q_norm_w = lw.q_norm_w; sb.k_norm_w = lw.k_norm_w; sb.norm_eps = c.ln_eps; }
+    sb.q_scale = q_scale;
     PF_TRY(run(s, PF_KC_KV_SCATTER, [&] { return launch_kv_scatter(sb, st); }));
   }
   return PF_OK;
@@ -390,6 +408,12 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
   }
 
   const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
+  // The bf16 attention kernel has a variant that takes q already multiplied by log2(e) / sqrt(dh); the factor is folded
+  // into the fp32 step that writes q (GEMM epilogue, or the scatter kernel when it normalises / rotates).
+  const bool pre_ok = use_path(&c) == PATH_AUTO && pf::g_attn_variant == 0 && attn_mfma2_takes_prescaled_q(c.head_dim) &&
+                      g_fold_q_scale;
+  const float q_fold = 1.4426950408889634f / sqrtf((float)c.head_dim);
+  bool q_pre = false;
   // (cos, sin) of the RoPE angles of one image's rows, shared by all layers and images of the call: [text; image] rows
   // for the single-stream kind, the image rows alone for the two-stream kind (its text stream is not rotated)
   if (single)
@@ -404,12 +428,14 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       const int RT = B * R;
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xsrc, D, m, m + D, c.ln_eps, h, D, RT, D, 1, st, B > 1 ? R : 0, mstride); }));
       {
-        pf_status qs_ = qkv_project(s, h, lw, qkv, R, kb, vb, Tt, 0, row0_img, ws + w.rope, img_off, true);
+        const bool pre = pre_ok && qkv_route(s, h, lw, qkv, true) != ROUTE_SCATTER_PLAIN;
+        pf_status qs_ = qkv_project(s, h, lw, qkv, R, kb, vb, Tt, 0, row0_img, ws + w.rope, img_off, true, pre ? q_fold : 0.f);
         if (qs_ != PF_OK) return qs_;
+        q_pre = pre;
       }
       // MLP branch runs in parallel with attention: GELU(h W_up^T + b) lands right of the attention columns
       PF_TRY(gemm(s, PF_KC_GEMM_UP, h, D, lw.w_up, D, lw.b_up, a + (size_t)D * e, D + F, RT, F, D, 0, 0, nullptr, nullptr, 0, nullptr, 0));
-      PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D + F, R));
+      PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D + F, R, q_pre));
       PF_TRY(gemm(s, PF_KC_GEMM_DOWN, a, D + F, lw.w_down, D + F, lw.b_down, xbuf, D, RT, D, D + F, 1, 0, m + 2 * D, xsrc, D, nullptr, 0, nullptr, R));
       xsrc = xbuf;
       continue;
@@ -422,6 +448,13 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
     if (c.kind == PF_BLOCK_MMDIT_JOINT && Tt) streams[ns++] = Stream{&s->txt[l], s->mod(0, l), t_row0, Tt, 0};
     streams[ns++] = Stream{&s->img[l], s->mod(d.n_streams - 1, l), Tt ? i_row0 : 0, n_img, row0_img};
 
+    // q is handed over with the attention kernel's factor folded in only if every stream's projection rewrites q in fp32
+    q_pre = pre_ok;
+    for (int si = 0; si < ns && q_pre; ++si) {
+      const Stream &sm = streams[si];
+      const bool rot = d.rope && sm.lw == &s->img[l];
+      q_pre = qkv_route(s, h + sm.r0 * D * e, *sm.lw, qkv + sm.r0 * 3 * D * e, rot) != ROUTE_SCATTER_PLAIN;
+    }
     for (int si = 0; si < ns; ++si) {
       const Stream &sm = streams[si];
       const float *xs = xsrc + sm.r0 * D;
@@ -430,16 +463,16 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       PF_TRY(run(s, PF_KC_LN_MODULATE, [&] { return launch_ln_modulate(dt, xs, D, sm.m, sm.m + D, c.ln_eps, hs, D, B * sm.seg, D, 1, st, B > 1 ? sm.seg : 0, mstride); }));
       const bool rot = d.rope && sm.lw == &s->img[l];   // image stream of a rotating two-stream block
       pf_status qs_ = qkv_project(s, hs, *sm.lw, qs, sm.seg, kb, vb, 0, 0, sm.brow0, rot ? ws + w.rope : nullptr,
-                                  rot ? img_off : -1, rot);
+                                  rot ? img_off : -1, rot, q_pre ? q_fold : 0.f);
       if (qs_ != PF_OK) return qs_;
     }
     if (B == 1) {
       // one image: the text and image rows are adjacent, one launch covers both
-      PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R));
+      PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R, q_pre));
     } else {
       for (int si = 0; si < ns; ++si)
         PF_TRY(attention(s, PF_KC_ATTENTION, qkv + streams[si].r0 * 3 * D * e, 3 * D, kb, vb, d.Lkv, d.Lp,
-                         a + streams[si].r0 * D * e, D, streams[si].seg));
+                         a + streams[si].r0 * D * e, D, streams[si].seg, q_pre));
     }
     for (int si = 0; si < ns; ++si) {
       const Stream &sm = streams[si];
@@ -764,7 +797,8 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 namespace pf { extern int g_gemm_tile_override, g_wavek_min_k, g_wavek_max_tiles; }
 namespace pf { extern int g_attn_variant; extern int g_attn_stages; }
 extern "C" void pf_tune_gemm_tile(int id) {
-  if (id >= 500) pf::g_wavek_max_tiles = (id - 500) * 16;
+  if (id >= 800) g_fold_q_scale = id - 800;
+  else if (id >= 500) pf::g_wavek_max_tiles = (id - 500) * 16;
   else if (id >= 400) pf::g_wavek_min_k = (id - 400) * 64;
   else if (id >= 300) pf::g_attn_stages = id - 300;
   else if (id >= 200) g_fuse_kv_route = id - 200;
