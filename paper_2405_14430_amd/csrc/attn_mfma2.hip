@@ -181,21 +181,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
 
   // fragment addressing, loop invariant: address = row base + ((chunk ^ key) << 4); the chunk's low bit is the
   // half-wave index, so it is folded into the per-lane key and the rest of the chunk index is a compile-time XOR mask
-  int krow_off[2], kx[2];
+  // Per-lane parts of the LDS addresses, one register per K=16 slice: the row block, the V^T column block and the stage
+  // only add constants (a block of 32 rows is a whole number of swizzle periods), which go into the offset field of the
+  // LDS reads (where it fits their 16 bits: always with two stages), so a fragment read costs no address arithmetic.
+  const unsigned char *kaddr[C::KS16];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    int r = b * 32 + l32;
-    krow_off[b] = r * C::KROW;
-    kx[b] = (hi ^ C::kkey(r)) << 4;
-  }
-  int vrow_off[C::CB], vx[C::CB];
+  for (int ks = 0; ks < C::KS16; ++ks)
+    kaddr[ks] = smem + l32 * C::KROW + ((((hi ^ C::kkey(l32)) << 4)) ^ (ks << 5));
+  const unsigned char *ktail_addr = smem + l32 * C::KROW + C::KS16 * 32 + hi * 8;
+  const unsigned char *vaddr[4];
 #pragma unroll
-  for (int cb = 0; cb < C::CB; ++cb) {
-    int r = cb * 32 + l32;
-    vrow_off[cb] = C::K_BYTES + r * 128;
-    vx[cb] = (hi ^ ((r >> 1) & 7)) << 4;
-  }
-
+  for (int j = 0; j < 4; ++j) vaddr[j] = smem + C::K_BYTES + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
 
   auto tile_step = [&](int t, auto stage_c) {
@@ -205,7 +201,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
     __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the stage of tile t-1
     asm volatile("" ::: "memory");
     if (t + NS - 1 < t_end) issue((stage + NS - 1) % NS, t + NS - 1);
-    const unsigned char *st = smem + stage * C::STAGE;
 
     // ---- S^T = K . Q^T for the two 32-row blocks of the tile
     f32x16 sacc[2];
@@ -215,11 +210,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
       for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < C::KS16; ++ks) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + krow_off[b] + (kx[b] ^ (ks << 5)));
+        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kaddr[ks] + (stage * C::STAGE + b * 32 * C::KROW));
         sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], (PRE && ks == 0) ? cneg : sacc[b], 0, 0, 0);
       }
       if constexpr (C::TAIL8) {
-        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(st + krow_off[b] + C::KS16 * 32 + hi * 8);
+        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(ktail_addr + (stage * C::STAGE + b * 32 * C::KROW));
         sacc[b] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, kf4),
                                                            __builtin_bit_cast(short4v, qtail), sacc[b], 0, 0, 0);
       }
@@ -315,7 +310,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          bf16x8 vf = *reinterpret_cast<const bf16x8 *>(st + vrow_off[cb] + (vx[cb] ^ ((2 * b + s2) << 5)));
+          bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vaddr[2 * b + s2] + (stage * C::STAGE + cb * 32 * 128));
           oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[b][s2], oacc[cb], 0, 0, 0);
         }
     }
