@@ -273,6 +273,9 @@ pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void
  * between the last stage of diffusion step t and the first stage of step t-1 (Sec. 2, Eq. 1; Euler form).  n = 0 is a
  * no-op (pointers may then be NULL); n < 0 gives PF_ERR_SHAPE, a NULL pointer with n > 0 PF_ERR_NULL. */
 pf_status pf_op_axpy(const float *x, const float *y, float alpha, float *out, int64_t n, void *stream);
+/* out[i] = a * x[i] + b * y[i]: the same update for samplers whose rule is linear in x_t and the network output with a
+ * coefficient on x_t (deterministic DDIM-type rules).  Same argument rules as pf_op_axpy. */
+pf_status pf_op_axpby(const float *x, const float *y, float a, float b, float *out, int64_t n, void *stream);
 
 /* Name of the kernel instance the library's tile heuristic runs for a GEMM of this shape (static string; matches the
  * template instance seen in a rocprofv3 kernel trace).  Used by the benchmark to group GEMM launches by kernel. */

@@ -55,7 +55,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention",
-           "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image"]
+           "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
 
 _lib = None
 
@@ -117,6 +117,8 @@ def load_library():
     lib.pf_gemm_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.pf_op_axpy.restype = i32
     lib.pf_op_axpy.argtypes = [vp, vp, f32, vp, i64, vp]
+    lib.pf_op_axpby.restype = i32
+    lib.pf_op_axpby.argtypes = [vp, vp, f32, f32, vp, i64, vp]
     lib.pf_tune_gemm_tile.restype = None
     lib.pf_tune_gemm_tile.argtypes = [i32]
     _lib = lib
@@ -337,4 +339,11 @@ def pf_op_axpy(x, y, alpha, out=None):
     lib = load_library()
     out = torch.empty_like(x) if out is None else out
     _ok(lib.pf_op_axpy(_ptr(x), _ptr(y), float(alpha), _ptr(out), x.numel(), _stream_ptr()))
+    return out
+
+
+def pf_op_axpby(x, y, a, b, out=None):
+    lib = load_library()
+    out = torch.empty_like(x) if out is None else out
+    _ok(lib.pf_op_axpby(_ptr(x), _ptr(y), float(a), float(b), _ptr(out), x.numel(), _stream_ptr()))
     return out

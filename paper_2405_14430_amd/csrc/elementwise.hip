@@ -384,20 +384,25 @@ hipError_t launch_rope_table(void *tab, int rows, int n_text, int tok0, int grid
 }
 
 // ------------------------------------------------------------------------------------------------
-// out = x + alpha * y: the element-wise sampler update between diffusion steps (Sec. 2, Eq. 1, Euler form)
+// out = a * x + b * y: the element-wise sampler update between diffusion steps (Sec. 2, Eq. 1): a = 1 is the Euler /
+// flow form x + dt * eps, general (a, b) covers the deterministic DDIM-type rules that are linear in x_t and eps
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void axpy_kernel(const float *__restrict__ x, const float *__restrict__ y, float alpha,
-                                                   float *__restrict__ out, int64_t n) {
+__global__ __launch_bounds__(256) void axpby_kernel(const float *__restrict__ x, const float *__restrict__ y, float a,
+                                                    float b, float *__restrict__ out, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * 256;
-  for (; i < n; i += stride) out[i] = fmaf(alpha, y[i], x[i]);
+  if (a == 1.0f) {
+    for (; i < n; i += stride) out[i] = fmaf(b, y[i], x[i]);
+  } else {
+    for (; i < n; i += stride) out[i] = fmaf(b, y[i], a * x[i]);
+  }
 }
 
-hipError_t launch_axpy(const float *x, const float *y, float alpha, float *out, int64_t n, hipStream_t s) {
+hipError_t launch_axpby(const float *x, const float *y, float a, float b, float *out, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + 255) / 256;
   if (blocks > 16384) blocks = 16384;
-  axpy_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(x, y, alpha, out, n);
+  axpby_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(x, y, a, b, out, n);
   return hipGetLastError();
 }
 

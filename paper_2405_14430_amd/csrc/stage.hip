@@ -758,7 +758,14 @@ pf_status pf_op_axpy(const float *x, const float *y, float alpha, float *out, in
   if (n < 0) return PF_ERR_SHAPE;
   if (n == 0) return PF_OK;
   if (!x || !y || !out) return PF_ERR_NULL;
-  return launch_axpy(x, y, alpha, out, n, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+  return launch_axpby(x, y, 1.0f, alpha, out, n, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+pf_status pf_op_axpby(const float *x, const float *y, float a, float b, float *out, int64_t n, void *stream) {
+  if (n < 0) return PF_ERR_SHAPE;
+  if (n == 0) return PF_OK;
+  if (!x || !y || !out) return PF_ERR_NULL;
+  return launch_axpby(x, y, a, b, out, n, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 
 const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K) {

@@ -46,6 +46,11 @@ def test_axpy_matches_update_rule():
         assert got.shape == (n,)
         if n:
             assert np.max(np.abs(got.double().cpu().numpy() - ref)) <= 2.0 ** -23 * np.max(np.abs(ref))
+    from paper_2405_14430_amd import pf_op_axpby
+    xa, ea = rng.normal(size=777).astype(np.float32), rng.normal(size=777).astype(np.float32)
+    got = pf_op_axpby(_f32(xa), _f32(ea), 0.75, -0.3)
+    ref = 0.75 * xa.astype(np.float64) - 0.3 * ea.astype(np.float64)
+    assert np.max(np.abs(got.double().cpu().numpy() - ref)) <= 2.0 ** -22 * np.max(np.abs(ref))
     x = _f32(rng.normal(size=1000).astype(np.float32))
     keep = x.clone()
     pf_op_axpy(x, x.clone(), 0.5, out=x)                 # in place
