@@ -106,3 +106,27 @@ def scheme_costs(scheme, p, hs, L, N, kv_bytes_per_layer, param_bytes):
     }
     comm, overlap, params, kv = rows[scheme]
     return {"comm_elements": comm, "overlap": overlap, "param_bytes": params, "kv_bytes": kv}
+
+
+class CfgPipelineOracle:
+    """Classifier-free guidance on top of the patch pipeline: every step runs the stage stack on the same latent with
+    the conditional and the unconditional conditioning (two independent sets of K/V buffers, shared weights; the paper
+    runs the two on separate device groups, Sec. 4.1.3), combines eps = eps_u + scale * (eps_c - eps_u) and applies
+    the update."""
+
+    def __init__(self, cfg, stage_layers):
+        self.cond_pipe = PipelineOracle(cfg, stage_layers)
+        self.uncond_pipe = PipelineOracle(cfg, stage_layers)
+
+    def run(self, x_T, conds_c, conds_u, dts, scale, warmup_steps=1, text_c=None, text_u=None):
+        x = np.array(x_T, F64)
+        trace = []
+        for s, (cc, cu, dt) in enumerate(zip(conds_c, conds_u, dts)):
+            if s < warmup_steps:
+                ec, eu = self.cond_pipe.warmup_step(x, cc, text_c), self.uncond_pipe.warmup_step(x, cu, text_u)
+            else:
+                ec, eu = self.cond_pipe.pipelined_step(x, cc, text_c), self.uncond_pipe.pipelined_step(x, cu, text_u)
+            eps = eu + float(scale) * (ec - eu)
+            trace.append(eps)
+            x = euler_update(x, eps, dt)
+        return x, trace

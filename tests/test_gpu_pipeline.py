@@ -88,3 +88,35 @@ def test_sampling_loop_matches_oracle(name, N, S):
         assert torch.equal(x2, x)
     finally:
         pipe.destroy()
+
+
+@pytest.mark.parametrize("name,S", [("K0f", 3), ("K1f", 2), ("K3f", 2), ("C2s", 3), ("C3s", 2)])
+def test_guided_sampling_loop_matches_oracle(name, S):
+    """Classifier-free guidance: conditional and unconditional pass share every call (batch 2)."""
+    from paper_2405_14430_amd.pipeline import CfgPipeline
+    from oracle.pf_pipeline import CfgPipelineOracle
+    cfg = wl.CONFIGS[name]
+    ucfg = wl.variant(cfg, seed=cfg["seed"] + 100)
+    N, scale = 2, 3.0
+    W = wl.make_weights(cfg, n_layers=N * cfg["n_layers"])
+    A, U = wl.make_activations(cfg), wl.make_activations(ucfg)
+    conds_c, dts = wl.make_sampling(cfg, S)
+    conds_u, _ = wl.make_sampling(ucfg, S)
+    _log("guided pipeline", name, "S", S)
+    ref, trace = CfgPipelineOracle(cfg, wl.split_stages(W, N)).run(A["x"], conds_c, conds_u, dts, scale, 1, A["text"], U["text"])
+    pipe = CfgPipeline(cfg, wl.split_stages(W, N))
+    text2 = None
+    if A["text"] is not None:
+        text2 = _f32(np.stack([A["text"], U["text"]], 0))
+        if cfg["kind"] == 1:
+            text2 = text2.to(torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32)
+    conds2 = [_f32(np.stack([c, u], 0)) for c, u in zip(conds_c, conds_u)]
+    tol = TOL[cfg["dtype"]] * (1.0 + 2.0 * (scale - 1.0))     # the guided eps amplifies the difference of two passes
+    try:
+        x = pipe.run(_f32(A["x"]), conds2, dts, scale, warmup_steps=1, text2=text2)
+        torch.cuda.synchronize()
+        e = _relerr(x, ref)
+        _log("  final latent err", e)
+        assert e < tol * S
+    finally:
+        pipe.destroy()

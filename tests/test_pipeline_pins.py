@@ -173,3 +173,33 @@ def test_cost_table_relations_and_library_buffer_size():
     stage_bytes = lib.pf_stage_kv_bytes(C.byref(B.make_config(cfg)))
     cross = 2 * 128 * hs * 2 * cfg["n_layers"]      # cached text K/V of the cross-attention (120 keys padded to 128)
     assert stage_bytes - cross == pf_["kv_bytes"]   # 4096 rows need no padding
+
+
+@pytest.mark.parametrize("name", ["K0f", "K1f"])
+def test_cfg_loop_with_one_patch_is_the_exact_guided_sampler(name):
+    """M = 1: the guided pipeline equals two full forwards per step combined as eps_u + s (eps_c - eps_u)."""
+    cfg = wl.variant(wl.CONFIGS[name], n_patches=1)
+    W = wl.make_weights(cfg, n_layers=2 * cfg["n_layers"])
+    A = wl.make_activations(cfg)
+    U = wl.make_activations(wl.variant(cfg, seed=cfg["seed"] + 100))     # the unconditional branch's conditioning
+    conds_c, dts = wl.make_sampling(cfg, 3)
+    conds_u, _ = wl.make_sampling(wl.variant(cfg, seed=cfg["seed"] + 100), 3)
+    scale = 4.5
+    got, _ = pp.CfgPipelineOracle(cfg, wl.split_stages(W, 2)).run(A["x"], conds_c, conds_u, dts, scale, 1, A["text"], U["text"])
+    x = np.array(A["x"], np.float64)
+    for cc, cu, dt in zip(conds_c, conds_u, dts):
+        ec, _ = full_forward(cfg, W, x, cc, A["text"])
+        eu, _ = full_forward(cfg, W, x, cu, U["text"])
+        x = x + dt * (eu + scale * (ec - eu))
+    assert _rel(got, x) < 1e-9
+
+
+def test_cfg_scale_one_is_the_conditional_pipeline():
+    cfg = wl.CONFIGS["K0f"]
+    W = wl.make_weights(cfg, n_layers=2 * cfg["n_layers"])
+    A = wl.make_activations(cfg)
+    conds_c, dts = wl.make_sampling(cfg, 3)
+    conds_u, _ = wl.make_sampling(wl.variant(cfg, seed=77), 3)
+    a, _ = pp.CfgPipelineOracle(cfg, wl.split_stages(W, 2)).run(A["x"], conds_c, conds_u, dts, 1.0)
+    b, _ = pp.PipelineOracle(cfg, wl.split_stages(W, 2)).run(A["x"], conds_c, dts)
+    assert _rel(a, b) < 1e-12
