@@ -325,17 +325,38 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
   int i = (int)(id / cpr), ch = (int)(id % cpr) * 4;
   int h = ch / dh;
   const float *ml = ws + (size_t)splits * nq * d;
-  float M = -INFINITY;
-  for (int sidx = 0; sidx < splits; ++sidx) M = fmaxf(M, ml[(((size_t)sidx * nq + i) * H + h) * 2]);
-  float L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int sidx = 0; sidx < splits; ++sidx) {
-    const float *p = ml + (((size_t)sidx * nq + i) * H + h) * 2;
-    float m = p[0], l = p[1];
-    if (l <= 0.f) continue;  // split saw no key
-    float wgt = expf(m - M);
-    L += l * wgt;
-    float4 v = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
-    o[0] += v.x * wgt; o[1] += v.y * wgt; o[2] += v.z * wgt; o[3] += v.w * wgt;
+  // Eight splits at a time, every load of the group issued before the first use: the loads of one thread are
+  // independent, so a group costs one memory latency instead of one per split.  A split that saw no key (l <= 0) may
+  // never have written its O rows: its values are dropped by selection, not by a zero weight.
+  constexpr int G = 8;
+  float M = -INFINITY, L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < splits; s0 += G) {
+    float2 p[G];
+    float4 v[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int sidx = s0 + j < splits ? s0 + j : splits - 1;
+      p[j] = *reinterpret_cast<const float2 *>(ml + (((size_t)sidx * nq + i) * H + h) * 2);
+      v[j] = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
+    }
+    float Mg = M;
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+      if (s0 + j < splits && p[j].y > 0.f) Mg = fmaxf(Mg, p[j].x);
+    if (Mg == -INFINITY) continue;   // no key in this group or before it
+    const float keep = expf(M - Mg);  // 0 for M = -inf
+    L *= keep;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) o[t] *= keep;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const bool live = s0 + j < splits && p[j].y > 0.f;
+      const float wgt = live ? expf(p[j].x - Mg) : 0.f;
+      L += live ? p[j].y * wgt : 0.f;
+      o[0] += live ? v[j].x * wgt : 0.f; o[1] += live ? v[j].y * wgt : 0.f;
+      o[2] += live ? v[j].z * wgt : 0.f; o[3] += live ? v[j].w * wgt : 0.f;
+    }
+    M = Mg;
   }
   float inv = 1.f / L;
   const int img = h / hpi;
