@@ -312,7 +312,9 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
  * Values 100 + v select the attention kernel generation instead (100 = default); 200 / 201 switch the fused K/V
  * routing of the QKV projection off / on; 300 + s pins the attention ring depth (300 = default); 400 + k sets the
  * smallest K (in units of 64) and 500 + t the largest tile count (in units of 16 tiles of 64 x 64) for which the
- * wave-split-K GEMM kernel is chosen; 800 / 801 switch the folding of the softmax exponent factor into q off / on. */
+ * wave-split-K GEMM kernel is chosen (t < 100); 600 + s pins the key-split count of the stage's attention launches
+ * (600 = heuristic; still capped at one split per four key tiles); 700 / 701 / 702: 256-query attention workgroups
+ * by launch size / never / always; 800 / 801 switch the folding of the softmax exponent factor into q off / on. */
 void pf_tune_gemm_tile(int id);
 
 #ifdef __cplusplus

@@ -1,7 +1,9 @@
 // Flash-style patch attention for gfx950, head sizes 64 / 72 / 128 (bf16 operands, fp32 accumulation and softmax).
 //
 // The patch's queries attend over ALL rows of the layer's K/V buffer, fresh and stale alike (PipeFusion Sec. 3.3).
-// Per workgroup: 128 queries (4 wavefronts x 32) of one head and one split of the key range.  The arithmetic layout is
+// Per workgroup: 32 queries per wavefront, 4 wavefronts (128 queries, two workgroups per CU) or 8 (256 queries, one
+// workgroup per CU whose K/V tiles then serve twice as many queries: half the L2 -> LDS bytes per flop, and the LDS that
+// a second workgroup would need goes into a deeper ring), of one head and one split of the key range.  The layout is
 // the transposed one (a lane owns one query column):
 //   S^T[kv][q] = K[kv][:] . Q[q][:]        A = K tile (LDS), B = Q fragments (registers)
 //   O^T[c][q] += V^T[c][kv] . P^T[kv][q]   A = V^T tile (LDS), B = P^T straight from the S^T accumulator registers
@@ -23,10 +25,10 @@
 namespace pf {
 
 int g_attn_stages = 0;   // tuning hook: 0 = default ring depth, 2 / 3 = forced
+int g_attn_wide = 0;     // tuning hook: 0 = 256-query workgroups when the launch has enough queries, 1 = never, 2 = always
 
 namespace {
 
-constexpr int TQ = 128;
 constexpr int TK = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -41,8 +43,9 @@ __device__ __forceinline__ void lds_load16(const void *g, unsigned char *lds_wav
                                    (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
 }
 
-template <int DH>
+template <int DH, int NW = 4>
 struct Cfg {
+  static constexpr int TQ = 32 * NW;                     // queries per workgroup
   static constexpr int KS16 = DH / 16;
   static constexpr bool TAIL8 = (DH % 16) == 8;
   static constexpr int KROW = DH * 2;                    // bytes per K tile row
@@ -54,7 +57,7 @@ struct Cfg {
   static constexpr int V_BYTES = V_ROWS * 128;
   static constexpr int V_INSTR = DH / 8;                 // 8 rows of 128 B per instruction
   static constexpr int STAGE = K_BYTES + V_BYTES;
-  static constexpr int LK = (K_INSTR + 3) / 4, LV = (V_INSTR + 3) / 4;   // instructions per wave
+  static constexpr int LK = (K_INSTR + NW - 1) / NW, LV = (V_INSTR + NW - 1) / NW;   // instructions per wave
   static constexpr int LPS = LK + LV;
   // Head sizes that leave padding rows in the V^T tile (72 -> 96 rows) get the softmax denominator for free: padding
   // row DH holds ones, so row DH of O^T accumulates sum_j P[j][q] in the matrix pipe (with the same rescaling as the
@@ -70,14 +73,15 @@ struct Cfg {
 // epilogue, so q is rounded to bf16 once either way; scaling bf16 queries here would round them a second time and
 // costs accuracy on peaked softmaxes).  The score MFMAs then deliver exponents of 2 and the softmax of an element
 // needs no multiply-add.
-template <int DH, int NS, bool PRE>
-__global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__restrict__ q, int64_t ldq,
+template <int DH, int NS, bool PRE, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(const bf16_t *__restrict__ q, int64_t ldq,
                                                             const bf16_t *__restrict__ kbuf,
                                                             const bf16_t *__restrict__ vtbuf, int kv_rows, int Lp, int H,
                                                             bf16_t *__restrict__ out, int64_t ldo, int nq, int splits,
                                                             int qtiles, float *__restrict__ ws, int hpi) {
   // H counts heads over all images of the call (image-major, hpi heads per image); q / out rows are image-major too
-  using C = Cfg<DH>;
+  using C = Cfg<DH, NW>;
+  constexpr int TQ = C::TQ, NT = 64 * NW;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -98,7 +102,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   // ---- zero the V^T padding rows (never written by the tile loads) of every stage
   if constexpr (C::V_ROWS > DH) {
     constexpr int PADB = (C::V_ROWS - DH) * 128;
-    for (int e = tid; e < NS * PADB / 16; e += 256) {
+    for (int e = tid; e < NS * PADB / 16; e += NT) {
       int st = e / (PADB / 16), o = e % (PADB / 16);
       const unsigned fill = (C::ONES_ROW && o < 8) ? 0x3F803F80u : 0u;   // first padding row: bf16 1.0 in every key column
       *reinterpret_cast<uint4 *>(smem + st * C::STAGE + C::K_BYTES + DH * 128 + o * 16) = make_uint4(fill, fill, fill, fill);
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   unsigned char *kdst[C::LK];
 #pragma unroll
   for (int i = 0; i < C::LK; ++i) {
-    int ins = min(i * 4 + wave, C::K_INSTR - 1);          // surplus slots repeat the last instruction (same data)
+    int ins = min(i * NW + wave, C::K_INSTR - 1);         // surplus slots repeat the last instruction (same data)
     int off = ins * 1024 + lane * 16;
     int r = off / C::KROW, p = (off % C::KROW) >> 4;
     koff[i] = r * C::KROW + ((p ^ C::kkey(r)) << 4);
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   unsigned char *vdst[C::LV];
 #pragma unroll
   for (int i = 0; i < C::LV; ++i) {
-    int ins = min(i * 4 + wave, C::V_INSTR - 1);
+    int ins = min(i * NW + wave, C::V_INSTR - 1);
     int r = ins * 8 + (lane >> 3), p = lane & 7;
     voff[i] = (int64_t)r * Lp + ((p ^ ((r >> 1) & 7)) << 3);
     vdst[i] = smem + C::K_BYTES + ins * 1024;
@@ -139,8 +143,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
 #pragma unroll
     for (int i = 0; i < C::LV; ++i) lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
   };
+  // tiles in flight ahead of the one being worked on: NS - 1, or NS - 2 for the 8-wave schedule (see its loop)
 #pragma unroll
-  for (int i = 0; i < NS - 1; ++i)
+  for (int i = 0; i < (NW == 8 ? NS - 2 : NS - 1); ++i)
     if (t_begin + i < t_end) issue(i, t_begin + i);
 
   // ---- Q fragments (B operand): lane holds query q0 + l32, channels ks*16 + 8*hi .. +7
@@ -194,14 +199,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   for (int j = 0; j < 4; ++j) vaddr[j] = smem + C::K_BYTES + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
 
-  auto tile_step = [&](int t, auto stage_c) {
+  bf16x8 pf[2][2];   // P^T fragments of the tile whose PV product comes next
+  // ---- S^T = K . Q^T, online softmax and the P^T fragments of tile t (K from `stage`)
+  auto qk_softmax = [&](int t, auto stage_c) {
     constexpr int stage = decltype(stage_c)::value;
-    // tile t has landed once at most min(NS-2, tiles left after t) later tiles of this wave are still in flight
-    if (NS >= 3 && t + 1 < t_end) wait_vmcnt<(NS >= 3 ? C::LPS : 0)>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the stage of tile t-1
-    asm volatile("" ::: "memory");
-    if (t + NS - 1 < t_end) issue((stage + NS - 1) % NS, t + NS - 1);
-
     // ---- S^T = K . Q^T for the two 32-row blocks of the tile
     f32x16 sacc[2];
 #pragma unroll
@@ -294,7 +295,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
     }
     // ---- O^T += V^T . P^T.  For each K=16 step the half-waves trade registers so that lane-half `hi` holds the
     // weights of kv rows 16*step + 8*hi .. +7 (in order); V^T supplies the same rows with one 16-byte read.
-    bf16x8 pf[2][2];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -304,6 +304,10 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
         uint4 u = make_uint4(x0[0], x1[0], x0[1], x1[1]);
         pf[b][s2] = __builtin_bit_cast(bf16x8, u);
       }
+  };
+  // ---- O^T += V^T . P^T with the V^T tile of `stage` and the fragments qk_softmax left
+  auto pv = [&](auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
 #pragma unroll
     for (int cb = 0; cb < C::CB; ++cb) {
 #pragma unroll
@@ -315,11 +319,78 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
         }
     }
   };
+  if constexpr (NW == 4) {
+  auto tile_step = [&](int t, auto stage_c) {
+    constexpr int stage = decltype(stage_c)::value;
+    // tile t has landed once at most min(NS-2, tiles left after t) later tiles of this wave are still in flight
+    if (NS >= 4 && t + 2 < t_end) wait_vmcnt<(NS >= 4 ? 2 * C::LPS : 0)>();
+    else if (NS >= 3 && t + 1 < t_end) wait_vmcnt<(NS >= 3 ? C::LPS : 0)>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();         // ... for every wave; and every wave is done with the stage of tile t-1
+    asm volatile("" ::: "memory");
+    if (t + NS - 1 < t_end) issue((stage + NS - 1) % NS, t + NS - 1);
+
+    qk_softmax(t, stage_c);
+    pv(stage_c);
+  };
   for (int t = t_begin; t < t_end; t += NS) {
     tile_step(t, std::integral_constant<int, 0>{});
     if (t + 1 < t_end) tile_step(t + 1, std::integral_constant<int, 1>{});
     if constexpr (NS >= 3) {
       if (t + 2 < t_end) tile_step(t + 2, std::integral_constant<int, 2>{});
+    }
+    if constexpr (NS >= 4) {
+      if (t + 3 < t_end) tile_step(t + 3, std::integral_constant<int, 3>{});
+    }
+  }
+  } else {
+    // 8 waves, two per SIMD, one barrier per tile for all of them.  Waves 4..7 run the tile body rotated: PV of the
+    // previous tile, then S and softmax of this one, so that on every SIMD one wave is in its softmax (VALU) while the
+    // other is in a matrix phase.  The previous tile's V^T stage therefore stays live one step longer and the prefetch
+    // distance is NS - 2 tiles: at step t the loads of tile t + NS - 2 go into the stage tile t - 2 used.
+    static_assert(NW == 4 || NS == 4, "the 8-wave schedule is written for a four-stage ring");
+    const bool rot = wave >= 4;
+    // (the two schedules are separate loops so that neither pays for the other's live registers)
+    auto top = [&](int t, auto stage_c) {
+      constexpr int stage = decltype(stage_c)::value;
+      if (t + 1 < t_end) wait_vmcnt<C::LPS>(); else wait_vmcnt<0>();   // tile t landed; tile t + 1 may be in flight
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (t + NS - 2 < t_end) issue((stage + NS - 2) % NS, t + NS - 2);
+    };
+    if (!rot) {
+      auto step = [&](int t, auto stage_c) {
+        top(t, stage_c);
+        qk_softmax(t, stage_c);
+        pv(stage_c);
+      };
+      for (int t = t_begin; t < t_end; t += NS) {
+        step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < t_end) step(t + 1, std::integral_constant<int, 1>{});
+        if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
+        if (t + 3 < t_end) step(t + 3, std::integral_constant<int, 3>{});
+      }
+    } else {
+      auto step = [&](int t, auto stage_c) {
+        constexpr int stage = decltype(stage_c)::value;
+        top(t, stage_c);
+        if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+        qk_softmax(t, stage_c);
+      };
+      for (int t = t_begin; t < t_end; t += NS) {
+        step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < t_end) step(t + 1, std::integral_constant<int, 1>{});
+        if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
+        if (t + 3 < t_end) step(t + 3, std::integral_constant<int, 3>{});
+      }
+      if (t_end > t_begin) {
+        switch ((t_end - 1 - t_begin) % NS) {
+          case 0: pv(std::integral_constant<int, 0>{}); break;
+          case 1: pv(std::integral_constant<int, 1>{}); break;
+          case 2: pv(std::integral_constant<int, 2>{}); break;
+          default: pv(std::integral_constant<int, 3 % NS>{}); break;
+        }
+      }
     }
   }
   wait_vmcnt<0>();
@@ -366,13 +437,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma2_kernel(const bf16_t *__rest
   }
 }
 
-template <int DH, int NS, bool PRE = false>
+template <int DH, int NS, bool PRE = false, int NW = 4>
 hipError_t launch2(const AttnArgs &a, hipStream_t s) {
-  using C = Cfg<DH>;
+  using C = Cfg<DH, NW>;
+  constexpr int TQ = C::TQ;
+  static_assert(2 * C::LPS <= 63, "two tiles of loads must fit the vmcnt counter");
   constexpr int smem = NS * C::STAGE;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH, NS, PRE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH, NS, PRE, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_done = true;
@@ -380,7 +453,7 @@ hipError_t launch2(const AttnArgs &a, hipStream_t s) {
   const int qtiles = (a.nq + TQ - 1) / TQ;
   const int B = a.batch > 1 ? a.batch : 1;
   dim3 g(qtiles * a.n_heads * B * a.splits);
-  attn_mfma2_kernel<DH, NS, PRE><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
+  attn_mfma2_kernel<DH, NS, PRE, NW><<<g, 64 * NW, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf, (const bf16_t *)a.vtbuf,
                                              a.kv_rows, a.rows_padded, a.n_heads * B, (bf16_t *)a.out, a.ldo, a.nq, a.splits,
                                              qtiles, a.ws, a.n_heads);
   return hipGetLastError();
@@ -392,6 +465,12 @@ bool attn_mfma2_takes_prescaled_q(int head_dim) {
   return (head_dim == 64 || head_dim == 72 || head_dim == 128) && (g_attn_stages == 0 || g_attn_stages == 2);
 }
 
+// Queries per workgroup the bf16 kernel will use for a launch of nq query rows per image (the split heuristic needs it).
+int attn_mfma2_qtile(int nq) {
+  if (g_attn_stages != 0) return 128;                 // the pinned ring depths exist for the 4-wave kernel only
+  return g_attn_wide == 2 || (g_attn_wide == 0 && nq >= 1024) ? 256 : 128;
+}
+
 bool attn_mfma2_supported(const AttnArgs &a) {
   return (a.head_dim == 64 || a.head_dim == 72 || a.head_dim == 128) && a.rows_padded % TK == 0;
 }
@@ -401,6 +480,17 @@ hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s) {
   if (a.nq <= 0) return hipSuccess;
   // Two stages by default: in-stage A/B runs on MI355X showed no gain from a third stage for dh = 64 / 72 (1626 vs
   // 1635 us on the 64K-key PixArt stage) and a loss for dh = 128, where it halves the workgroups per CU (430 vs 565 us).
+  if (attn_mfma2_qtile(a.nq) == 256) {
+    // four stages of 32 KB (dh = 128) are 128 KB of the CU's 160 KB
+    if (a.q_prescaled) {
+      if (a.head_dim == 64) return launch2<64, 4, true, 8>(a, s);
+      if (a.head_dim == 72) return launch2<72, 4, true, 8>(a, s);
+      return launch2<128, 4, true, 8>(a, s);
+    }
+    if (a.head_dim == 64) return launch2<64, 4, false, 8>(a, s);
+    if (a.head_dim == 72) return launch2<72, 4, false, 8>(a, s);
+    return launch2<128, 4, false, 8>(a, s);
+  }
   const int ns = g_attn_stages ? g_attn_stages : 2;
   if (a.q_prescaled && ns != 2) return hipErrorInvalidValue;   // only the two-stage kernels have the variant
   if (a.q_prescaled) {

@@ -63,12 +63,44 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int n_ma
   return true;
 }
 
-// Epilogue over a finished fp32 tile held row-major in LDS (row stride TLD floats).
-template <int BM, int BN, int TLD, int NT = 256>
+// Residual and gate operands of a mode-1 epilogue, fetched by the thread that will use them before the K loop starts, so
+// that their memory latency runs under the loop instead of after it (the residual rows were written by an earlier
+// kernel and are in no cache).  Only for tiles small enough that a thread owns at most IT 8-column groups.  A tile is
+// read and written by its own workgroup only, so reading R early is safe when the GEMM updates it in place.
+template <int BM, int BN, int NT>
+struct EpiOperands {
+  static constexpr int IT = BM * BN / 8 / NT;
+  float4 r[IT][2], g[IT][2];
+  bool on;
+  __device__ __forceinline__ void fetch(int m0, int n0, int M, int N, const Epilogue<bf16_t> &epi, bool vec_ok) {
+    on = vec_ok && epi.mode == 1;
+    if (!on) return;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int grp = threadIdx.x + it * NT;
+      const int row = m0 + grp / (BN / 8), col = n0 + (grp % (BN / 8)) * 8;
+      if (row >= M || col + 8 > N) continue;
+      const float *rp = epi.R + (size_t)row * epi.ldr + col;
+      r[it][0] = *reinterpret_cast<const float4 *>(rp); r[it][1] = *reinterpret_cast<const float4 *>(rp + 4);
+      if (epi.gate) {
+        const float *gp = epi.gate_of(row) + col;
+        g[it][0] = *reinterpret_cast<const float4 *>(gp); g[it][1] = *reinterpret_cast<const float4 *>(gp + 4);
+      }
+    }
+  }
+};
+
+// Epilogue over a finished fp32 tile held row-major in LDS (row stride TLD floats).  PRE: residual / gate operands
+// come from `ops` (fetched earlier) when ops->on.
+template <int BM, int BN, int TLD, int NT = 256, bool PRE = false>
 __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0, int M, int N, const Epilogue<bf16_t> &epi,
-                                              bool vec_ok) {
+                                              bool vec_ok, const EpiOperands<BM, BN, NT> *ops = nullptr) {
   constexpr int GROUPS = BM * BN / 8;
-  for (int g = threadIdx.x; g < GROUPS; g += NT) {
+  constexpr int IT = (GROUPS + NT - 1) / NT, UNR = PRE ? IT : 1;
+#pragma unroll UNR
+  for (int it = 0; it < IT; ++it) {
+    const int g = threadIdx.x + it * NT;
+    if (GROUPS % NT != 0 && g >= GROUPS) break;
     const int r = g / (BN / 8), c0 = (g % (BN / 8)) * 8;
     const int row = m0 + r, col = n0 + c0;
     if (row >= M || col >= N) continue;
@@ -127,12 +159,21 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
       for (int e = 0; e < 8; ++e) o[e] = (bf16_t)v[e];
       *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16_t *>(epi.C) + (size_t)row * epi.ldc + col) = o;
     } else {
-      const float *rp = epi.R + (size_t)row * epi.ldr + col;
-      float4 r0 = *reinterpret_cast<const float4 *>(rp), r1 = *reinterpret_cast<const float4 *>(rp + 4);
+      float4 r0, r1, g0, g1;
+      bool have = false;
+      if constexpr (PRE) {
+        if (ops->on) { r0 = ops->r[it][0]; r1 = ops->r[it][1]; g0 = ops->g[it][0]; g1 = ops->g[it][1]; have = true; }
+      }
+      if (!have) {
+        const float *rp = epi.R + (size_t)row * epi.ldr + col;
+        r0 = *reinterpret_cast<const float4 *>(rp); r1 = *reinterpret_cast<const float4 *>(rp + 4);
+        if (epi.gate) {
+          const float *gp = epi.gate_of(row) + col;
+          g0 = *reinterpret_cast<const float4 *>(gp); g1 = *reinterpret_cast<const float4 *>(gp + 4);
+        }
+      }
       float x[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
       if (epi.gate) {
-        const float *gp = epi.gate_of(row) + col;
-        float4 g0 = *reinterpret_cast<const float4 *>(gp), g1 = *reinterpret_cast<const float4 *>(gp + 4);
         float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] += gg[e] * v[e];
@@ -239,6 +280,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
     for (int i = 0; i < LW; ++i) lds_load16(pw[i] + koff, sw + (i * NW + wave) * 1024);
   };
 
+  // small tiles: the epilogue's residual / gate operands are requested first, ahead of every tile load
+  constexpr bool EPRE = BM * BN / 8 / (64 * NW) <= 2;
+  EpiOperands<BM, BN, 64 * NW> eops;
+  if constexpr (EPRE) eops.fetch(m0, n0, M, N, epi, vec_ok != 0);
+
   f32x16 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -325,7 +371,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
           tile[(rbase - pass * RB + 8 * (r >> 2) + 4 * hi + (r & 3)) * TLD + wn * WN + j * 32 + l32] = acc[i][j][r];
     }
     __syncthreads();
-    tile_epilogue<RB, BN, TLD, 64 * NW>(tile, m0 + pass * RB, n0, M, N, epi, vec_ok != 0);
+    if constexpr (EPRE && RB == BM) tile_epilogue<BM, BN, TLD, 64 * NW, true>(tile, m0, n0, M, N, epi, vec_ok != 0, &eops);
+    else tile_epilogue<RB, BN, TLD, 64 * NW>(tile, m0 + pass * RB, n0, M, N, epi, vec_ok != 0);
   }
 }
 
@@ -384,6 +431,10 @@ __global__ __launch_bounds__(256) void gemm_wavek_kernel(const bf16_t *__restric
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  constexpr bool EPRE = BM * BN / 8 / 256 <= 2 && BM * BN / 8 >= 256;
+  EpiOperands<BM, BN, 256> eops;
+  if constexpr (EPRE) eops.fetch(m0, n0, M, N, epi, vec_ok != 0);
 
   if (my_nk > 0) issue(0, 0);
   if (my_nk > 1) issue(1, 1);
@@ -445,7 +496,8 @@ __global__ __launch_bounds__(256) void gemm_wavek_kernel(const bf16_t *__restric
     *reinterpret_cast<float4 *>(p0 + r * TLD + c) = s0;
   }
   __syncthreads();
-  tile_epilogue<BM, BN, TLD>(p0, m0, n0, M, N, epi, vec_ok != 0);
+  if constexpr (EPRE) tile_epilogue<BM, BN, TLD, 256, true>(p0, m0, n0, M, N, epi, vec_ok != 0, &eops);
+  else tile_epilogue<BM, BN, TLD>(p0, m0, n0, M, N, epi, vec_ok != 0);
 }
 
 bool vec_epilogue_ok(const GemmArgs &a) {

@@ -101,6 +101,8 @@ hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
 bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS variant for head sizes 64 / 72 / 128
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s);
+int attn_mfma2_qtile(int nq);                              // queries per workgroup it will use for nq query rows per image
+extern int g_attn_variant;                                 // tuning hook: 0 = newest attention kernel that supports the shape
 bool attn_mfma2_takes_prescaled_q(int head_dim);           // its kernel for this head size has a prescaled-q variant
 hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s);   // picks between the two
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);

@@ -85,25 +85,29 @@ Derived derive(const pf_config *c) {
 
 int use_path(const pf_config *c) { return (c->dtype == PF_BF16 && c->kernel_path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT; }
 
-// Split of the key range of an attention launch.  The chip holds 512 attention workgroups at a time (two per CU), so
-// a launch runs in ceil(workgroups / 512) rounds; the split count is picked to minimise a small cost model in units of
+// Split of the key range of an attention launch.  The chip holds 512 attention workgroups of 128 queries at a time (two
+// per CU; 256 of the 256-query kind), so a launch runs in ceil(workgroups / 512) rounds; the split count is picked to minimise a small cost model in units of
 // one key tile: rounds x (tiles per split + fixed per-workgroup cost), a penalty for a first round that leaves CUs with
 // a single workgroup (no second wave per SIMD to overlap with), and the combine pass that grows with the split count.
 // Measured on MI355X: Flux-scale patch (384 blocks) 4 splits 478 us vs 2 splits 503 us vs none 583 us; SD3-scale patch
 // (96 blocks) 5 splits 34 us vs 6 splits 38 us.
-int choose_splits(int path, int nq, int H, int kv_rows) {
-  const int qtile = path == PATH_SIMT ? 64 : 128;
+int g_force_splits = 0;   // tuning hook: > 0 replaces the heuristic's split count (still capped by the key tiles)
+int choose_splits(int path, int nq, int H, int kv_rows, int head_dim) {
+  const bool gen2 = path != PATH_SIMT && pf::g_attn_variant == 0 && (head_dim == 64 || head_dim == 72 || head_dim == 128);
+  const int qtile = path == PATH_SIMT ? 64 : (gen2 ? attn_mfma2_qtile(nq) : 128);
+  const int resident = qtile == 256 ? 256 : 512;   // workgroups the chip holds at a time
   const int ktile = path == PATH_SIMT ? 32 : 64;
   const int64_t blocks = (int64_t)((nq + qtile - 1) / qtile) * H;
   const int tiles = (kv_rows + ktile - 1) / ktile;
   int cap = tiles / 4;  // at least four tiles per split
   if (cap > 16) cap = 16;
+  if (g_force_splits > 0) return g_force_splits < (cap < 1 ? 1 : cap) ? g_force_splits : (cap < 1 ? 1 : cap);
   int best = 1;
   double best_cost = 1e300;
   for (int sp = 1; sp <= (cap < 1 ? 1 : cap); ++sp) {
     const int64_t wgs = blocks * sp;
-    const int64_t rounds = (wgs + 511) / 512;
-    const double fill = wgs >= 512 ? 1.0 : (double)wgs / 512.0;
+    const int64_t rounds = (wgs + resident - 1) / resident;
+    const double fill = wgs >= resident ? 1.0 : (double)wgs / resident;
     double cost = (double)rounds * ((tiles + sp - 1) / sp + 4) * (1.0 + 0.5 * (1.0 - fill));
     if (sp > 1) cost += 2.0 + 0.5 * sp;
     if (cost < best_cost - 1e-9) { best_cost = cost; best = sp; }
@@ -153,10 +157,10 @@ WsLayout ws_layout(const pf_config *c, const Derived &d) {
   int shapes[5] = {d.n, d.n + d.Tj, d.Lkv, d.Tj > 0 ? d.Tj : d.n, c->seq_img};
   const int HB = c->n_heads * d.B;
   for (int nq : shapes) {
-    size_t b = attention_ws_bytes(nq, HB, c->head_dim, choose_splits(path, nq, HB, d.Lkv));
+    size_t b = attention_ws_bytes(nq, HB, c->head_dim, choose_splits(path, nq, HB, d.Lkv, c->head_dim));
     if (b > ab) ab = b;
     if (c->kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
-      b = attention_ws_bytes(nq, HB, c->head_dim, choose_splits(path, nq, HB, d.T));
+      b = attention_ws_bytes(nq, HB, c->head_dim, choose_splits(path, nq, HB, d.T, c->head_dim));
       if (b > ab) ab = b;
     }
   }
@@ -260,7 +264,7 @@ hipError_t gemm(pf_stage *s, int cls, const void *A, int64_t lda, const void *W,
 int plan_splits(const pf_stage *s, int nq, int kv_rows) {
   const int path = use_path(&s->cfg);
   const int HB = s->cfg.n_heads * s->d.B;
-  int splits = choose_splits(path, nq, HB, kv_rows);
+  int splits = choose_splits(path, nq, HB, kv_rows, s->cfg.head_dim);
   while (splits > 1 && attention_ws_bytes(nq, HB, s->cfg.head_dim, splits) > s->w.attn_bytes) --splits;
   return splits;
 }
@@ -802,9 +806,11 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 }  // extern "C"
 
 namespace pf { extern int g_gemm_tile_override, g_wavek_min_k, g_wavek_max_tiles; }
-namespace pf { extern int g_attn_variant; extern int g_attn_stages; }
+namespace pf { extern int g_attn_stages, g_attn_wide; }
 extern "C" void pf_tune_gemm_tile(int id) {
   if (id >= 800) g_fold_q_scale = id - 800;
+  else if (id >= 700) pf::g_attn_wide = id - 700;
+  else if (id >= 600) g_force_splits = id - 600;
   else if (id >= 500) pf::g_wavek_max_tiles = (id - 500) * 16;
   else if (id >= 400) pf::g_wavek_min_k = (id - 400) * 64;
   else if (id >= 300) pf::g_attn_stages = id - 300;
