@@ -80,6 +80,10 @@ CONFIGS = {
                 seq_img=1080, grid_h=30, grid_w=36, n_patches=4, text_len=77, seed=26, qk_norm=1, joint_rope=1),
     "C4n": _cfg(kind=3, dtype="bf16", n_layers=2, hidden=384, n_heads=3, head_dim=128, mlp_dim=1536,
                 seq_img=1500, grid_h=30, grid_w=50, n_patches=5, text_len=45, seed=27, qk_norm=1),
+    # hidden size a multiple of 64: every GEMM of the block, the cross-attention projections included, takes the
+    # direct-to-LDS kernels (C2s / C5s have K = 288 and fall back to the register-staged GEMM)
+    "C2x": _cfg(kind=1, dtype="bf16", n_layers=2, hidden=576, n_heads=8, head_dim=72, mlp_dim=1152,
+                seq_img=1200, grid_h=30, grid_w=40, n_patches=4, text_len=37, cross_dim=160, seed=29),
     "C3r": _cfg(kind=2, dtype="bf16", n_layers=2, hidden=256, n_heads=4, head_dim=64, mlp_dim=1024,
                 seq_img=1080, grid_h=30, grid_w=36, n_patches=4, text_len=77, seed=28, joint_rope=1),
 }
