@@ -139,11 +139,18 @@ typedef struct pf_layer_weights {
  *             is attended to.
  *   text_out: kinds 2, 3 with text != NULL: float [T, d] receives the text rows after the stage
  *             (may alias text).  Otherwise ignored.
+ *   same_cond: pf_stage_patch_forward only.  Non-zero: `cond` holds the same values as in the previous call
+ *             on this stage (pf_kv_init's warm-up pass included) - the M patch calls of one diffusion step
+ *             share the timestep embedding (Sec. 3.3) - so the stage keeps the modulation vectors it derived
+ *             then and does not read `cond` (it may be NULL).  Vectors that the previous calls did not derive
+ *             (the text stream's, when no text rows rode along) are derived from `cond`, which must then not
+ *             be NULL.  Zero: they are derived anew.  The claim is the caller's; it is not checked.
  */
 typedef struct {
   const float *cond;
   const void *text;
   float *text_out;
+  int32_t same_cond;
 } pf_cond;
 
 /* Size of the caller-allocated K/V buffer / workspace for this configuration, in bytes

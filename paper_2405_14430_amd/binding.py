@@ -40,7 +40,7 @@ PfLayerWeights._fields_ = [(n, C.c_void_p) for n in _W_FIELDS] + [("txt", C.POIN
 
 
 class PfCond(C.Structure):
-    _fields_ = [("cond", C.c_void_p), ("text", C.c_void_p), ("text_out", C.c_void_p)]
+    _fields_ = [("cond", C.c_void_p), ("text", C.c_void_p), ("text_out", C.c_void_p), ("same_cond", C.c_int32)]
 
 
 class PfKvView(C.Structure):
@@ -205,9 +205,9 @@ class Stage:
         if st != 0:
             raise PfError(st, self.lib.pf_last_error(self.h).decode())
 
-    def _cond(self, cond, text, text_out):
+    def _cond(self, cond, text, text_out, same_cond=False):
         return PfCond(cond=None if cond is None else cond.data_ptr(), text=None if text is None else text.data_ptr(),
-                      text_out=None if text_out is None else text_out.data_ptr())
+                      text_out=None if text_out is None else text_out.data_ptr(), same_cond=int(bool(same_cond)))
 
     def kv_init(self, x_prev=None, cond=None, text=None, want_output=False):
         """x_prev/cond/text: device tensors (x_prev, cond, joint text: float32; kind-1 text: stage dtype).  A stage with
@@ -218,11 +218,13 @@ class Stage:
         self._check(self.lib.pf_kv_init(self.h, _ptr(x_prev), C.byref(pc), _ptr(y)))
         return (y, tout) if want_output else None
 
-    def patch_forward(self, x_patch, cond, p, text=None, out=None, text_out=None):
+    def patch_forward(self, x_patch, cond, p, text=None, out=None, text_out=None, same_cond=False):
+        """same_cond: `cond` has the values of this stage's previous call (the other patches of the same diffusion
+        step): the stage reuses its modulation vectors instead of deriving them again."""
         y = torch.empty_like(x_patch) if out is None else out
         if self.joint and text is not None and text_out is None:
             text_out = torch.empty_like(text)
-        pc = self._cond(cond, text if self.joint else None, text_out)
+        pc = self._cond(cond, text if self.joint else None, text_out, same_cond)
         self._check(self.lib.pf_stage_patch_forward(self.h, _ptr(x_patch), C.byref(pc), int(p), _ptr(y)))
         return (y, text_out) if (self.joint and text is not None) else y
 

@@ -181,6 +181,7 @@ struct pf_stage {
   char *ws;
   hipStream_t stream;
   bool ready = false;
+  bool mod_valid[2] = {false, false};   // per stream: the modulation vectors in the workspace belong to the last cond
   std::string err;
   // profiling
   bool prof = false;
@@ -356,7 +357,7 @@ hipError_t copy_blocks(float *dst, size_t dst_pitch, const float *src, size_t sr
 // single-stream kind (one weight set for both), all text rows then all image rows for the MMDiT kind (one weight set
 // per stream, so each stream is one contiguous GEMM operand).
 pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const float *cond, const float *text,
-                  float *y_img, float *text_out) {
+                  float *y_img, float *text_out, bool same_cond = false) {
   const pf_config &c = s->cfg;
   const Derived &d = s->d;
   const WsLayout &w = s->w;
@@ -399,16 +400,26 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
       mb.count = 0;
       return e2;
     };
+    // streams whose vectors must be derived in this call: all that run, unless the caller vouches for the cond
+    bool need[2] = {false, false};
+    for (int si = 0; si < d.n_streams; ++si) {
+      const bool runs = !(c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt);   // text stream idle without text rows
+      need[si] = runs && !(same_cond && s->mod_valid[si]);
+      if (!same_cond) s->mod_valid[si] = false;
+      if (need[si] && !cond) return fail(s, PF_ERR_NULL, "cond is NULL but modulation vectors have to be derived");
+    }
     for (int b = 0; b < B; ++b)
       for (int l = 0; l < c.n_layers; ++l)
         for (int si = 0; si < d.n_streams; ++si) {
-          if (c.kind == PF_BLOCK_MMDIT_JOINT && si == 0 && !Tt) continue;   // text stream idle
+          if (!need[si]) continue;
           const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
           mb.w[mb.count] = lw.w_mod; mb.b[mb.count] = lw.b_mod; mb.c[mb.count] = cond + b * cdim;
           mb.out[mb.count] = s->mod(si, l, b);
           if (++mb.count == ModBatch::kMax) PF_TRY(flush());
         }
     PF_TRY(flush());
+    for (int si = 0; si < d.n_streams; ++si)
+      if (need[si]) s->mod_valid[si] = true;
   }
 
   const int row0_img = d.Tj + img_off;   // buffer row of the first image row of this call
@@ -575,6 +586,7 @@ pf_status pf_kv_init(pf_stage *s, const float *x_prev, const pf_cond *cp, float 
   }
   s->err.clear();
   s->chain_open = false;   // other work may have been enqueued on the stream since the last call
+  s->mod_valid[0] = s->mod_valid[1] = false;
   PF_TRY(run(s, PF_KC_COPY, [&] { return launch_fill_zero(s->kv, kv_layer_bytes(&c, d) * c.n_layers, s->stream); }));
   if (c.kind == PF_BLOCK_ADALN_SINGLE_XATTN) {
     // text keys/values of every layer's cross-attention, computed once
@@ -603,7 +615,7 @@ pf_status pf_kv_init(pf_stage *s, const float *x_prev, const pf_cond *cp, float 
 
 pf_status pf_stage_patch_forward(pf_stage *s, const float *x_patch, const pf_cond *cond, int patch_idx, float *y_patch) {
   if (!s) return PF_ERR_NULL;
-  if (!x_patch || !y_patch || !cond || !cond->cond) return fail(s, PF_ERR_NULL, "null argument to pf_stage_patch_forward");
+  if (!x_patch || !y_patch || !cond || (!cond->cond && !cond->same_cond)) return fail(s, PF_ERR_NULL, "null argument to pf_stage_patch_forward");
   if (!s->ready) return fail(s, PF_ERR_STATE, "pf_kv_init must run before pf_stage_patch_forward");
   if (patch_idx < 0 || patch_idx >= s->cfg.n_patches) return fail(s, PF_ERR_RANGE, "patch index out of range");
   const bool joint_text = s->d.Tj && cond->text;
@@ -611,7 +623,7 @@ pf_status pf_stage_patch_forward(pf_stage *s, const float *x_patch, const pf_con
   s->err.clear();
   s->chain_open = false;   // other work may have been enqueued on the stream since the last call
   return forward(s, x_patch, s->d.n, patch_idx * s->d.n, cond->cond, joint_text ? (const float *)cond->text : nullptr,
-                 y_patch, joint_text ? cond->text_out : nullptr);
+                 y_patch, joint_text ? cond->text_out : nullptr, cond->same_cond != 0);
 }
 
 static pf_status fill_view(const pf_stage *s, int layer, int image, bool cross, pf_kv_view_t *out) {

@@ -44,7 +44,9 @@ class Pipeline:
         return self.eps
 
     def pipelined_step(self, x, cond, text=None):
-        """One step after warm-up.  eps rows of patch p are written straight into self.eps by the last stage."""
+        """One step after warm-up.  eps rows of patch p are written straight into self.eps by the last stage.  The
+        timestep embedding is the same for all M patches of the step: every stage derives its modulation vectors on
+        patch 0 and keeps them for the rest."""
         n = self.n
         for p in range(self.M):
             src = x[p * n:(p + 1) * n]
@@ -52,10 +54,10 @@ class Pipeline:
             for i, st in enumerate(self.stages):
                 dst = self.eps[p * n:(p + 1) * n] if i == self.N - 1 else self._h[i & 1]
                 if tsrc is not None:
-                    st.patch_forward(src, cond, p, text=tsrc, out=dst, text_out=self._t[i & 1])
+                    st.patch_forward(src, cond, p, text=tsrc, out=dst, text_out=self._t[i & 1], same_cond=p > 0)
                     tsrc = self._t[i & 1]
                 else:
-                    st.patch_forward(src, cond, p, out=dst)
+                    st.patch_forward(src, cond, p, out=dst, same_cond=p > 0)
                 src = dst
         return self.eps
 
@@ -123,10 +125,10 @@ class CfgPipeline:
             for i, st in enumerate(self.stages):
                 dst = self._h[i & 1]
                 if tsrc is not None:
-                    st.patch_forward(src, cond2, p, text=tsrc, out=dst, text_out=self._t[i & 1])
+                    st.patch_forward(src, cond2, p, text=tsrc, out=dst, text_out=self._t[i & 1], same_cond=p > 0)
                     tsrc = self._t[i & 1]
                 else:
-                    st.patch_forward(src, cond2, p, out=dst)
+                    st.patch_forward(src, cond2, p, out=dst, same_cond=p > 0)
                 src = dst
             self.eps2[:, p * n:(p + 1) * n].copy_(src)
         return self._combine(scale)

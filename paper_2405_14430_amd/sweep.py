@@ -118,7 +118,8 @@ def sweep_batch(name, batches, iters, warmup):
 
 
 def time_full_step(name, M, n_stages, steps):
-    """One diffusion step after warm-up on one device: M patches x N stages + the update."""
+    """One diffusion step after warm-up on one device: M patches x N stages + the update (the stages derive their
+    modulation vectors on the first patch of the step and keep them for the others)."""
     import torch
     from .pipeline import Pipeline
     base = wl.variant(wl.CONFIGS[name], n_patches=M)

@@ -206,6 +206,56 @@ def test_m1_equals_fresh_everywhere_on_gpu():
     st.destroy()
 
 
+@pytest.mark.parametrize("name", ["K0f", "K1f", "K3f", "C2s", "C4s"])
+def test_same_cond_reuses_the_modulation_vectors(name):
+    """The patch calls of one diffusion step share the timestep embedding: after the first, same_cond = 1 makes the stage
+    keep its modulation vectors (cond is not read: a NULL pointer, or other values, change nothing)."""
+    _log("same_cond", name)
+    cfg = wl.CONFIGS[name]
+    W, A = wl.make_weights(cfg), wl.make_activations(cfg)
+    orc, st = StageOracle(cfg, W), _pkg().Stage(cfg, W)
+    cond_prev, cond = _f32(A["cond"] * 0.5), _f32(A["cond"])
+    text = _text_dev(cfg, A)
+    joint = cfg["kind"] in (2, 3)
+    orc.kv_init(A["x_prev"], A["cond"] * 0.5, A["text"])
+    st.kv_init(_f32(A["x_prev"]), cond_prev, text)
+    n = wl.patch_rows(cfg)
+    other = torch.full_like(cond, 7.0)
+    for p in range(cfg["n_patches"]):
+        xp = A["x"][p * n:(p + 1) * n]
+        kw = dict(text=text) if (joint and p == 0) else {}
+        y = st.patch_forward(_f32(xp), cond if p == 0 else (None if p == 1 else other), p, same_cond=p > 0, **kw)
+        ref = orc.patch_forward(xp, A["cond"], p, **(dict(text=A["text"]) if (joint and p == 0) else {}))
+        if joint and p == 0:
+            y, ref = y[0], ref[0]
+        torch.cuda.synchronize()
+        assert _relerr(y, ref) < TOL[cfg["dtype"]], p
+    st.destroy()
+
+
+def test_same_cond_still_derives_what_is_missing():
+    """Two-stream block: a call without text rows derives only the image stream's vectors; a later call that brings the
+    text rows and says same_cond must still derive the text stream's (from cond, which then may not be NULL)."""
+    pkg = _pkg()
+    cfg = wl.CONFIGS["K2f"]
+    W, A = wl.make_weights(cfg), wl.make_activations(cfg)
+    orc, st = StageOracle(cfg, W), pkg.Stage(cfg, W)
+    n = wl.patch_rows(cfg)
+    st.kv_init(None)
+    orc.kv_init(None, None, None)
+    cond, text = _f32(A["cond"]), _f32(A["text"])
+    y1 = st.patch_forward(_f32(A["x"][n:2 * n]), cond, 1)
+    assert _relerr(y1, orc.patch_forward(A["x"][n:2 * n], A["cond"], 1)) < TOL["f32"]
+    with pytest.raises(pkg.PfError) as e:
+        st.patch_forward(_f32(A["x"][:n]), None, 0, text=text, same_cond=True)
+    assert e.value.status == -1
+    y0, t0 = st.patch_forward(_f32(A["x"][:n]), cond, 0, text=text, same_cond=True)
+    r0, rt = orc.patch_forward(A["x"][:n], A["cond"], 0, text=A["text"])
+    torch.cuda.synchronize()
+    assert _relerr(y0, r0) < TOL["f32"] and _relerr(t0, rt) < TOL["f32"]
+    st.destroy()
+
+
 def test_state_and_argument_errors():
     pkg = _pkg()
     cfg = wl.CONFIGS["K0f"]
