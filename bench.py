@@ -162,7 +162,7 @@ def main():
         if c in gemm_shapes:
             sym = st.lib.pf_gemm_kernel_name(dtc, args.path, n, gemm_shapes[c][0], gemm_shapes[c][1]).decode()
         else:
-            sym = ("attn_mfma2_kernel<%d>" % cfg["head_dim"]) if (dtc and not args.path) else "attn_simt_kernel"
+            sym = st.lib.pf_attention_kernel_name(dtc, args.path, cfg["head_dim"], n, 1 if c == "attention" else 0).decode()
         g = groups.setdefault(sym, {"ms": 0.0, "launches": 0.0, "flops": 0.0, "classes": []})
         g["ms"] += kernels[c]["ms_per_step"]
         g["launches"] += kernels[c]["launches_per_step"]

@@ -287,6 +287,9 @@ pf_status pf_op_axpby(const float *x, const float *y, float a, float b, float *o
 /* Name of the kernel instance the library's tile heuristic runs for a GEMM of this shape (static string; matches the
  * template instance seen in a rocprofv3 kernel trace).  Used by the benchmark to group GEMM launches by kernel. */
 const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K);
+/* Likewise for an attention launch of nq query rows per image (q_prescaled: the stage's self-attention, whose queries
+ * carry the softmax factor; 0: plain queries).  The string is per-thread storage, valid until the next call. */
+const char *pf_attention_kernel_name(int dtype, int path, int head_dim, int nq, int q_prescaled);
 
 /*
  * Write rows of fresh keys/values into a layer's buffer.  qkv dtype [rows, 3d] (row stride ld): q | k | v.

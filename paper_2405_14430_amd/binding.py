@@ -54,7 +54,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_patch_forward", "pf_kv_view", "pf_xattn_kv_view", "pf_stage_attention_plan", "pf_stage_set_stream",
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
-           "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention",
+           "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention", "pf_attention_kernel_name",
            "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
 
 _lib = None
@@ -109,6 +109,8 @@ def load_library():
                                vp, i64, vp]
     lib.pf_op_kv_scatter.restype = i32
     lib.pf_op_kv_scatter.argtypes = [i32, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, f32, vp]
+    lib.pf_attention_kernel_name.restype = C.c_char_p
+    lib.pf_attention_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.pf_op_attention_ws_bytes.restype = sz
     lib.pf_op_attention_ws_bytes.argtypes = [i32, i32, i32, i32]
     lib.pf_op_attention.restype = i32

@@ -103,6 +103,7 @@ bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS vari
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s);
 int attn_mfma2_qtile(int nq);                              // queries per workgroup it will use for nq query rows per image
 extern int g_attn_variant;                                 // tuning hook: 0 = newest attention kernel that supports the shape
+extern int g_attn_stages, g_attn_wide;                     // tuning hooks of that kernel: ring depth, workgroup width
 bool attn_mfma2_takes_prescaled_q(int head_dim);           // its kernel for this head size has a prescaled-q variant
 hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s);   // picks between the two
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);

@@ -791,6 +791,16 @@ const char *pf_gemm_kernel_name(int dtype, int path, int M, int N, int K) {
   return gemm_mfma_dl_supported(g) ? gemm_mfma_dl_variant_name(g) : "gemm_mfma_kernel";
 }
 
+const char *pf_attention_kernel_name(int dtype, int path, int head_dim, int nq, int q_prescaled) {
+  if (dtype != PF_BF16 || path != PF_PATH_AUTO) return "attn_simt_kernel";
+  if (pf::g_attn_variant != 0 || !(head_dim == 64 || head_dim == 72 || head_dim == 128)) return "attn_mfma_kernel";
+  static thread_local char name[64];
+  const bool wide = attn_mfma2_qtile(nq) == 256;
+  const int ns = wide ? 4 : (pf::g_attn_stages ? pf::g_attn_stages : 2);
+  snprintf(name, sizeof(name), "attn_mfma2_kernel<%d,%d,%s,%d>", head_dim, ns, q_prescaled ? "true" : "false", wide ? 8 : 4);
+  return name;
+}
+
 size_t pf_op_attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
   return attention_ws_bytes(nq, n_heads, head_dim, splits);
 }
@@ -818,7 +828,6 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 }  // extern "C"
 
 namespace pf { extern int g_gemm_tile_override, g_wavek_min_k, g_wavek_max_tiles; }
-namespace pf { extern int g_attn_stages, g_attn_wide; }
 extern "C" void pf_tune_gemm_tile(int id) {
   if (id >= 800) g_fold_q_scale = id - 800;
   else if (id >= 700) pf::g_attn_wide = id - 700;
