@@ -278,6 +278,26 @@ def test_attention(dtype, path, H, dh, nq, Lkv, splits, gain):
     assert _relerr(got, po.attention(q, k, v, H)) < TOL[dtype]
 
 
+@pytest.mark.parametrize("dh", [64, 72, 128])
+@pytest.mark.parametrize("nq,Lkv,splits,gain", [(1030, 50, 1, 1.0), (1024, 128, 1, 1.0), (1100, 190, 1, 4.0), (1281, 256, 1, 1.0),
+                                                (1030, 300, 1, 1.0), (1030, 700, 1, 4.0), (1100, 1300, 3, 1.0),
+                                                (1025, 2000, 2, 8.0)])
+def test_attention_256_query_workgroups(dh, nq, Lkv, splits, gain):
+    """Launches of at least 1024 query rows take the 8-wave kernel (256 queries per workgroup, four-stage ring, half of
+    the waves on the rotated schedule): key-tile counts of every residue mod 4, ragged query and key tails, key splits."""
+    _log("attention wide", dh, nq, Lkv, splits, gain)
+    H = 2
+    rng = _rng(dh * 1009 + nq * 13 + Lkv)
+    q, k, v = _draw(rng, (nq, H * dh), BF, gain), _draw(rng, (Lkv, H * dh), BF), _draw(rng, (Lkv, H * dh), BF)
+    K, Vt, Lp = _kv_buffers(k, v, H, dh, BF)
+    got = _pkg().pf_op_attention(_dev(q, BF), K, Vt, Lkv, Lp, H, dh, splits=splits)
+    torch.cuda.synchronize()
+    assert _pkg().load_library().pf_attention_kernel_name(1, 0, dh, nq, 0).decode().endswith(",8>")
+    # 10^5 outputs stored in bf16: the storage rounding of a 4.5-sigma element alone is 2^-8 * 4.5 = 1.8e-2 rms, so the
+    # bar here is one bf16 rounding of the value plus half the 2e-2 rms bar for the arithmetic
+    assert _close(got, po.attention(q, k, v, H), BF, slack=1e-2)
+
+
 def test_attention_ignores_finite_padding_rows():
     """Rows beyond kv_rows never contribute, whatever finite values they hold."""
     H, dh, nq, Lkv = 2, 72, 50, 300
