@@ -42,20 +42,29 @@ __device__ __forceinline__ void modulation_body(const T *__restrict__ w, const T
   __syncthreads();
   constexpr int V = Vec16<T>::N;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  // 8 outputs per wave, 32 per block
-  for (int o = 0; o < 8; ++o) {
-    int j = blockIdx.x * 32 + wave * 8 + o;
-    if (j >= out_dim) break;
-    const T *row = w + (size_t)j * in_dim;
-    float acc = 0.f;
-    for (int i = lane * V; i < in_dim; i += 64 * V) {
-      float v[V];
-      Vec16<T>::load(row + i, v);
+  // 8 outputs per wave, 32 per block.  The eight weight rows are read side by side (eight 16-byte loads per lane in
+  // flight per step instead of one row after the other): the kernel is a stream over the [out_dim, in_dim] weights.
+  const int j0 = blockIdx.x * 32 + wave * 8;
+  if (j0 >= out_dim) return;
+  const T *rows[8];
 #pragma unroll
-      for (int t = 0; t < V; ++t) acc = fmaf(v[t], sc[i + t], acc);
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) mod[j] = acc + to_f32(b[j]);
+  for (int o = 0; o < 8; ++o) rows[o] = w + (size_t)min(j0 + o, out_dim - 1) * in_dim;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int i = lane * V; i < in_dim; i += 64 * V) {
+    float v[8][V];
+#pragma unroll
+    for (int o = 0; o < 8; ++o) Vec16<T>::load(rows[o] + i, v[o]);
+#pragma unroll
+    for (int o = 0; o < 8; ++o)
+#pragma unroll
+      for (int t = 0; t < V; ++t) acc[o] = fmaf(v[o][t], sc[i + t], acc[o]);
+  }
+#pragma unroll
+  for (int o = 0; o < 8; ++o) acc[o] = wave_sum(acc[o]);
+  if (lane == 0) {
+#pragma unroll
+    for (int o = 0; o < 8; ++o)
+      if (j0 + o < out_dim) mod[j0 + o] = acc[o] + to_f32(b[j0 + o]);
   }
 }
 
