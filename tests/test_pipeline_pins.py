@@ -72,6 +72,24 @@ def test_pipelined_steps_differ_from_exact_and_converge_with_step_size():
     assert errs[2] < 0.05
 
 
+def test_gap_to_exact_grows_with_the_patch_count_and_saturates():
+    """With M patches, patch p of a step sees M - 1 - p stale patches: on average a fraction (M - 1) / (2 M) of the
+    sequence is one step old.  M = 1 is exact; the gap grows with M and stays below twice the gap at M = 2 (the stale
+    fraction goes from 1/4 to at most 1/2)."""
+    base = wl.CONFIGS["K0f"]
+    errs = []
+    for M in (1, 2, 3, 6, 10):
+        cfg = wl.variant(base, n_patches=M)
+        W = wl.make_weights(cfg, n_layers=2 * cfg["n_layers"])
+        A = wl.make_activations(cfg)
+        conds, dts = wl.make_sampling(cfg, 4, dt_total=-0.05)
+        pipe = pp.PipelineOracle(cfg, wl.split_stages(W, 2))
+        got, _ = pipe.run(A["x"], conds, dts, warmup_steps=1, text=A["text"])
+        errs.append(_rel(got, _exact_loop(cfg, W, A["x"], conds, dts, A["text"])))
+    assert errs[0] < 1e-9
+    assert errs[1] < errs[2] < errs[3] < errs[4] < 2.0 * errs[1]
+
+
 @pytest.mark.parametrize("name,N", [("K0f", 3), ("K1f", 2), ("K2f", 3), ("K3f", 2)])
 def test_device_time_order_gives_the_same_values(name, N):
     """Emulate N devices: at micro-step tau device i runs item k = tau - i, items ordered (step, patch).  Calls are
