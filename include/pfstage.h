@@ -95,6 +95,11 @@ typedef struct {
                           be a power of two.  0: off */
   int32_t joint_rope;  /* kind 2 only, 1: RoPE on q and k of the image rows exactly as in kind 3 (text rows are not
                           rotated): the two-stream block of Flux-like models.  0: off */
+  int32_t txt_pre_only_last; /* kind 2 only, 1: in the stage's LAST layer the text stream only supplies keys and
+                          values - the final joint block of an MMDiT, whose text output nobody reads (the stage that
+                          holds the model's last block sets it).  That layer's txt weights are w_mod [2d, d] / b_mod
+                          [2d] (chunks shift, scale), w_qkv / b_qkv (the q rows are not used) and the q / k norm
+                          scales; its other txt pointers may be NULL.  The text rows leave the layer unchanged.  0: off */
 } pf_config;
 
 #define PF_MAX_BATCH 8

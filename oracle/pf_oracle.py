@@ -153,7 +153,11 @@ class StageOracle:
          n_patches, text_len, cross_dim, grid_h, grid_w, ln_eps, rope_theta,
          gelu_tanh; optional qk_norm (RMSNorm of q and k per head, before RoPE,
          eps = ln_eps, weights q_norm_w / k_norm_w [dh]) and joint_rope (kind 2:
-         RoPE on the image rows as in kind 3).
+         RoPE on the image rows as in kind 3) and txt_pre_only_last (kind 2: in
+         the stack's last block the text stream only supplies keys and values -
+         the final joint block of an MMDiT, whose text output nobody reads: its
+         modulation has two chunks [shift, scale], its rows are normalised,
+         modulated and projected to k, v, and pass through unchanged).
     layers: list of dicts of arrays, matrices stored [out_features, in_features]:
          w_mod,b_mod, w_qkv,b_qkv, w_o,b_o, w_up,b_up, w_down,b_down,
          xattn_* (kind 1), 'txt' sub-dict (kind 2).
@@ -183,6 +187,7 @@ class StageOracle:
         self.gw = int(cfg["grid_w"])
         self.qk_norm = bool(cfg.get("qk_norm", 0))
         self.joint_rope = bool(cfg.get("joint_rope", 0)) and self.kind == KIND_MMDIT_JOINT
+        self.txt_pre_only_last = bool(cfg.get("txt_pre_only_last", 0)) and self.kind == KIND_MMDIT_JOINT
         self.kbuf = [np.zeros((self.Lkv, self.d), F64) for _ in range(self.nl)]
         self.vbuf = [np.zeros((self.Lkv, self.d), F64) for _ in range(self.nl)]
         self.kc = [None] * self.nl     # kind 1: text keys / values of the cross-attention
@@ -259,6 +264,7 @@ class StageOracle:
             if kind == KIND_MMDIT_JOINT and xt is not None:
                 streams = [(xt, w["txt"]), (x, w)]       # text rows first, own weights
             mods, qs = [], []
+            pre_only = self.txt_pre_only_last and l == self.nl - 1      # text stream: keys and values only
             for si, (xs, ws) in enumerate(streams):
                 mod = self.modulation(ws, cond)
                 mods.append(mod)
@@ -278,10 +284,14 @@ class StageOracle:
                 else:
                     self.kbuf[l][row0:row0 + n] = k      # write before attend
                     self.vbuf[l][row0:row0 + n] = v
-                qs.append(q)
+                if not (pre_only and is_text):
+                    qs.append(q)
             a_all = attention(np.concatenate(qs, axis=0), self.kbuf[l], self.vbuf[l], H)
             new, r = [], 0
-            for (xs, ws), mod in zip(streams, mods):
+            for si, ((xs, ws), mod) in enumerate(zip(streams, mods)):
+                if pre_only and len(streams) == 2 and si == 0:
+                    new.append(xs)                       # no attention output, no MLP for these rows
+                    continue
                 a = a_all[r:r + xs.shape[0]]
                 r += xs.shape[0]
                 xs = xs + mod[2] * linear(a, ws["w_o"], ws["b_o"])

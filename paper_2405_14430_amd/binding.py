@@ -27,7 +27,7 @@ class PfConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("kind", "dtype", "n_layers", "hidden", "n_heads", "head_dim", "mlp_dim",
                                           "seq_img", "n_patches", "text_len", "cross_dim", "grid_h", "grid_w")] + \
                [("ln_eps", C.c_float), ("rope_theta", C.c_float), ("gelu_tanh", C.c_int32), ("kernel_path", C.c_int32), ("batch", C.c_int32),
-                ("qk_norm", C.c_int32), ("joint_rope", C.c_int32)]
+                ("qk_norm", C.c_int32), ("joint_rope", C.c_int32), ("txt_pre_only_last", C.c_int32)]
 
 
 class PfLayerWeights(C.Structure):
@@ -141,7 +141,8 @@ def make_config(cfg, kernel_path=PF_PATH_AUTO, n_layers=None):
                     cross_dim=cfg.get("cross_dim", 0), grid_h=cfg["grid_h"], grid_w=cfg["grid_w"],
                     ln_eps=cfg.get("ln_eps", 1e-6), rope_theta=cfg.get("rope_theta", 1e4),
                     gelu_tanh=cfg.get("gelu_tanh", 1), kernel_path=kernel_path, batch=cfg.get("batch", 1),
-                    qk_norm=cfg.get("qk_norm", 0), joint_rope=cfg.get("joint_rope", 0))
+                    qk_norm=cfg.get("qk_norm", 0), joint_rope=cfg.get("joint_rope", 0),
+                    txt_pre_only_last=cfg.get("txt_pre_only_last", 0))
 
 
 def torch_dtype(cfg):

@@ -57,6 +57,8 @@ const char *check_config(const pf_config *c, pf_status *st) {
   if (!(c->ln_eps > 0.f)) return "ln_eps must be > 0";
   if (c->joint_rope != 0 && c->joint_rope != 1) return "joint_rope must be 0 or 1";
   if (c->joint_rope && c->kind != PF_BLOCK_MMDIT_JOINT) return "joint_rope applies to kind 2 only (kind 3 always rotates)";
+  if (c->txt_pre_only_last != 0 && c->txt_pre_only_last != 1) return "txt_pre_only_last must be 0 or 1";
+  if (c->txt_pre_only_last && c->kind != PF_BLOCK_MMDIT_JOINT) return "txt_pre_only_last applies to kind 2 only";
   const bool rope = c->kind == PF_BLOCK_SINGLE_STREAM || c->joint_rope;
   if (rope && !(c->rope_theta > 1.f)) return "rope_theta must be > 1";
   if (rope && c->head_dim % 4) return "RoPE needs head_dim to be a multiple of 4";
@@ -394,9 +396,9 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
     const int out_dim = d.mod_chunks * D;
     const int table = c.kind == PF_BLOCK_ADALN_SINGLE_XATTN;
     const size_t cdim = table ? (size_t)6 * D : (size_t)D;
-    auto flush = [&]() -> hipError_t {
+    auto flush = [&](int od) -> hipError_t {
       if (mb.count == 0) return hipSuccess;
-      hipError_t e2 = run(s, PF_KC_MODULATION, [&] { return launch_modulation_batch(dt, mb, out_dim, D, table, st); });
+      hipError_t e2 = run(s, PF_KC_MODULATION, [&] { return launch_modulation_batch(dt, mb, od, D, table, st); });
       mb.count = 0;
       return e2;
     };
@@ -415,9 +417,17 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
           const pf_layer_weights &lw = (d.n_streams == 2 && si == 0) ? s->txt[l] : s->img[l];
           mb.w[mb.count] = lw.w_mod; mb.b[mb.count] = lw.b_mod; mb.c[mb.count] = cond + b * cdim;
           mb.out[mb.count] = s->mod(si, l, b);
-          if (++mb.count == ModBatch::kMax) PF_TRY(flush());
+          if (c.txt_pre_only_last && si == 0 && l == c.n_layers - 1 && d.n_streams == 2) {
+            // two chunks (shift, scale) instead of six: a launch of its own, the batch shares one output width
+            ModBatch one{};
+            one.w[0] = mb.w[mb.count]; one.b[0] = mb.b[mb.count]; one.c[0] = mb.c[mb.count]; one.out[0] = mb.out[mb.count];
+            one.count = 1;
+            PF_TRY(run(s, PF_KC_MODULATION, [&] { return launch_modulation_batch(dt, one, 2 * D, D, table, st); }));
+            continue;
+          }
+          if (++mb.count == ModBatch::kMax) PF_TRY(flush(out_dim));
         }
-    PF_TRY(flush());
+    PF_TRY(flush(out_dim));
     for (int si = 0; si < d.n_streams; ++si)
       if (need[si]) s->mod_valid[si] = true;
   }
@@ -463,6 +473,8 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
     if (c.kind == PF_BLOCK_MMDIT_JOINT && Tt) streams[ns++] = Stream{&s->txt[l], s->mod(0, l), t_row0, Tt, 0};
     streams[ns++] = Stream{&s->img[l], s->mod(d.n_streams - 1, l), Tt ? i_row0 : 0, n_img, row0_img};
 
+    // final joint block: the text rows (first stream) are projected to keys and values and nothing else
+    const bool txt_kv_only = c.txt_pre_only_last && l == c.n_layers - 1 && ns == 2;
     // q is handed over with the attention kernel's factor folded in only if every stream's projection rewrites q in fp32
     q_pre = pre_ok;
     for (int si = 0; si < ns && q_pre; ++si) {
@@ -481,15 +493,15 @@ pf_status forward(pf_stage *s, const float *x_img, int n_img, int img_off, const
                                   rot ? img_off : -1, rot, q_pre ? q_fold : 0.f);
       if (qs_ != PF_OK) return qs_;
     }
-    if (B == 1) {
+    if (B == 1 && !txt_kv_only) {
       // one image: the text and image rows are adjacent, one launch covers both
       PF_TRY(attention(s, PF_KC_ATTENTION, qkv, 3 * D, kb, vb, d.Lkv, d.Lp, a, D, R, q_pre));
     } else {
-      for (int si = 0; si < ns; ++si)
+      for (int si = txt_kv_only ? 1 : 0; si < ns; ++si)
         PF_TRY(attention(s, PF_KC_ATTENTION, qkv + streams[si].r0 * 3 * D * e, 3 * D, kb, vb, d.Lkv, d.Lp,
                          a + streams[si].r0 * D * e, D, streams[si].seg, q_pre));
     }
-    for (int si = 0; si < ns; ++si) {
+    for (int si = txt_kv_only ? 1 : 0; si < ns; ++si) {
       const Stream &sm = streams[si];
       const int nr = B * sm.seg;
       float *xs = xbuf + sm.r0 * D;
@@ -555,9 +567,11 @@ pf_status pf_stage_create(const pf_config *cfg, const pf_layer_weights *layers, 
     if (kind == PF_BLOCK_MMDIT_JOINT && !layers[l].txt) return fail(nullptr, PF_ERR_NULL, "kind 2 needs text-stream weights (txt)");
     for (const pf_layer_weights *lw : streams) {
       if (!lw) continue;
-      bool ok = lw->w_mod && lw->w_qkv && lw->b_qkv && lw->w_up && lw->b_up && lw->w_down && lw->b_down;
+      // the text stream of a final joint block only produces keys and values
+      const bool kv_only = cfg->txt_pre_only_last && l == cfg->n_layers - 1 && lw == streams[1];
+      bool ok = lw->w_mod && lw->w_qkv && lw->b_qkv && (kv_only || (lw->w_up && lw->b_up && lw->w_down && lw->b_down));
       if (kind != PF_BLOCK_ADALN_SINGLE_XATTN) ok = ok && lw->b_mod;
-      if (kind != PF_BLOCK_SINGLE_STREAM) ok = ok && lw->w_o && lw->b_o;
+      if (kind != PF_BLOCK_SINGLE_STREAM) ok = ok && (kv_only || (lw->w_o && lw->b_o));
       if (kind == PF_BLOCK_ADALN_SINGLE_XATTN)
         ok = ok && lw->xattn_wq && lw->xattn_bq && lw->xattn_wkv && lw->xattn_bkv && lw->xattn_wo && lw->xattn_bo;
       if (cfg->qk_norm) ok = ok && lw->q_norm_w && lw->k_norm_w;

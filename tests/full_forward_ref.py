@@ -63,7 +63,8 @@ def full_forward(cfg, layers, x, cond, text=None):
     xt = _t(text).clone() if (kind in (2, 3) and text is not None) else None
     ln = lambda z: Fn.layer_norm(z, (d,), eps=eps)
 
-    for w in layers:
+    for li, w in enumerate(layers):
+        pre_only = bool(cfg.get("txt_pre_only_last")) and kind == 2 and li == len(layers) - 1
         if kind == 3:
             T = xt.shape[0]
             rows = torch.cat([xt, x], 0)
@@ -101,9 +102,18 @@ def full_forward(cfg, layers, x, cond, text=None):
                             torch.stack([idx // cfg["grid_w"], idx % cfg["grid_w"]], 1).to(DT)], 0)
             qq = _rope_complex(qq.contiguous(), rc, H, cfg.get("rope_theta", 1e4))
             kk = _rope_complex(kk.contiguous(), rc, H, cfg.get("rope_theta", 1e4))
-        a_all = _mha(qq, kk, qkv[:, 2 * d:], H)
+        if pre_only:
+            # final joint block: only the image rows are queries; the text rows pass through
+            a_img = _mha(qq[xt.shape[0]:], kk, qkv[:, 2 * d:], H)
+            a_all = torch.cat([torch.zeros(xt.shape[0], d, dtype=DT), a_img], 0)
+        else:
+            a_all = _mha(qq, kk, qkv[:, 2 * d:], H)
         outs, r = [], 0
-        for (xs, ws), m in zip(streams, mods):
+        for si, ((xs, ws), m) in enumerate(zip(streams, mods)):
+            if pre_only and si == 0:
+                outs.append(xs)
+                r += xs.shape[0]
+                continue
             a = a_all[r:r + xs.shape[0]]
             r += xs.shape[0]
             xs = xs + m[2] * Fn.linear(a, _t(ws["w_o"]), _t(ws["b_o"]))

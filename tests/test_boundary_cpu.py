@@ -80,7 +80,7 @@ def test_batched_views_and_plan(lib):
     lib.pf_stage_destroy(h)
 
 
-BAD = [dict(qk_norm=2), dict(joint_rope=1), dict(qk_norm=1, head_dim=48, n_heads=8), dict(hidden=100), dict(n_patches=7), dict(head_dim=12, n_heads=32), dict(dtype_code=5), dict(kind=9),
+BAD = [dict(qk_norm=2), dict(joint_rope=1), dict(txt_pre_only_last=1), dict(txt_pre_only_last=3), dict(qk_norm=1, head_dim=48, n_heads=8), dict(hidden=100), dict(n_patches=7), dict(head_dim=12, n_heads=32), dict(dtype_code=5), dict(kind=9),
        dict(grid_w=3), dict(mlp_dim=100), dict(n_layers=0), dict(ln_eps=0.0)]
 
 

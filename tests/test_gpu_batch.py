@@ -49,7 +49,7 @@ def _stack(acts, key):
 
 
 CASES = [("K0f", 2, 0), ("K1f", 2, 0), ("K2f", 2, 0), ("K3f", 2, 0), ("K1f", 3, 0),
-         ("C2s", 2, 0), ("C2x", 2, 0), ("C3s", 2, 0), ("C4s", 2, 0), ("C5s", 2, 0), ("C2s", 2, 1), ("C3s", 3, 0),
+         ("C2s", 2, 0), ("C2x", 2, 0), ("C3p", 2, 0), ("C3s", 2, 0), ("C4s", 2, 0), ("C5s", 2, 0), ("C2s", 2, 1), ("C3s", 3, 0),
          ("K2n", 2, 0), ("C3n", 2, 0), ("C4n", 2, 0), ("C3r", 2, 0)]
 
 

@@ -56,7 +56,7 @@ def _natural(Kview):
     return Kview.double().cpu().numpy().reshape(r, H * dh)
 
 
-SMALL = ["C1", "K0f", "K1f", "K2f", "K3f", "C2s", "C3s", "C4s", "C5s", "K2n", "K3n", "C3n", "C4n", "C3r", "C2x"]
+SMALL = ["C1", "K0f", "K1f", "K2f", "K3f", "C2s", "C3s", "C4s", "C5s", "K2n", "K3n", "C3n", "C4n", "C3r", "C2x", "K2p", "C3p"]
 CASES = [(n, 0) for n in SMALL] + [(n, 1) for n in ("C2s", "C3s", "C4s")]
 
 

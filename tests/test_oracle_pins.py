@@ -15,7 +15,7 @@ import workloads as wl
 from oracle import pf_oracle as po
 from full_forward_ref import full_forward
 
-FP32_TWINS = ["K0f", "K1f", "K2f", "K3f", "K2n", "K3n"]   # K2n / K3n: q,k RMSNorm (and RoPE on the two-stream block)
+FP32_TWINS = ["K0f", "K1f", "K2f", "K3f", "K2n", "K3n", "K2p"]   # K2n / K3n: q,k RMSNorm (and RoPE on the two-stream block); K2p: final joint block
 RTOL = 1e-9
 
 

@@ -21,7 +21,7 @@ KIND_MMDIT_JOINT = 2         # SD3: two weight streams, one joint attention
 KIND_SINGLE_STREAM = 3       # Flux single-stream: parallel attn+MLP, 2-D RoPE
 
 _BASE = dict(text_len=0, cross_dim=0, ln_eps=1e-6, rope_theta=1e4, gelu_tanh=1,
-             w_std=0.02, qk_gain=1.0, cond_std=None, qk_norm=0, joint_rope=0)
+             w_std=0.02, qk_gain=1.0, cond_std=None, qk_norm=0, joint_rope=0, txt_pre_only_last=0)
 
 
 def _cfg(**kw):
@@ -80,6 +80,12 @@ CONFIGS = {
                 seq_img=1080, grid_h=30, grid_w=36, n_patches=4, text_len=77, seed=26, qk_norm=1, joint_rope=1),
     "C4n": _cfg(kind=3, dtype="bf16", n_layers=2, hidden=384, n_heads=3, head_dim=128, mlp_dim=1536,
                 seq_img=1500, grid_h=30, grid_w=50, n_patches=5, text_len=45, seed=27, qk_norm=1),
+    # final joint block of an MMDiT as the stage's last layer: its text stream only supplies keys and values
+    "K2p": _cfg(kind=2, dtype="f32", n_layers=2, hidden=128, n_heads=2, head_dim=64, mlp_dim=320,
+                seq_img=198, grid_h=11, grid_w=18, n_patches=3, text_len=29, w_std="fan_in", seed=30,
+                txt_pre_only_last=1),
+    "C3p": _cfg(kind=2, dtype="bf16", n_layers=2, hidden=256, n_heads=4, head_dim=64, mlp_dim=1024,
+                seq_img=1080, grid_h=30, grid_w=36, n_patches=4, text_len=77, seed=31, qk_norm=1, txt_pre_only_last=1),
     # hidden size a multiple of 64: every GEMM of the block, the cross-attention projections included, takes the
     # direct-to-LDS kernels (C2s / C5s have K = 288 and fall back to the register-staged GEMM)
     "C2x": _cfg(kind=1, dtype="bf16", n_layers=2, hidden=576, n_heads=8, head_dim=72, mlp_dim=1152,
@@ -168,10 +174,18 @@ def make_weights(cfg, n_layers=None):
     """List (one entry per layer) of dicts of float32 arrays; kind 2 layers carry a 'txt' sub-dict."""
     rng = np.random.Generator(np.random.Philox(key=int(cfg["seed"]) * 1000 + 1))
     layers = []
-    for _ in range(cfg["n_layers"] if n_layers is None else n_layers):
+    nl = cfg["n_layers"] if n_layers is None else n_layers
+    for l in range(nl):
         w = _stream_weights(cfg, rng)
         if cfg["kind"] == KIND_MMDIT_JOINT:
             w["txt"] = _stream_weights(cfg, rng)
+            if cfg.get("txt_pre_only_last") and l == nl - 1:
+                # final joint block: the text stream keeps only what produces its keys and values (modulation with two
+                # chunks [shift, scale], the QKV projection and the q / k norm scales)
+                t = w["txt"]
+                d = cfg["hidden"]
+                w["txt"] = {k: v for k, v in t.items() if k in ("w_qkv", "b_qkv", "q_norm_w", "k_norm_w")}
+                w["txt"]["w_mod"], w["txt"]["b_mod"] = t["w_mod"][: 2 * d].copy(), t["b_mod"][: 2 * d].copy()
         layers.append(w)
     return layers
 
