@@ -69,9 +69,10 @@ def test_ln_modulate(dtype, rows, d):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF])
-def test_modulation(dtype):
-    rng = _rng(5)
-    d, out = 1152, 6 * 1152 + 8
+@pytest.mark.parametrize("d,out", [(1152, 6 * 1152 + 8), (200, 37), (64, 3), (1536, 2 * 1536 + 1)])
+def test_modulation(dtype, d, out):
+    """Output widths that are no multiple of the eight rows a wave streams side by side, or of a block's 32."""
+    rng = _rng(5 + d + out)
     w, b, c = _draw(rng, (out, d), dtype, 0.02), _draw(rng, (out,), dtype, 0.02), _draw(rng, (d,), F32)
     got = _pkg().pf_op_modulation(_dev(w, dtype), _dev(b, dtype), _dev(c, F32))
     torch.cuda.synchronize()
@@ -258,8 +259,10 @@ def test_kv_scatter_qk_rmsnorm(dtype, H, dh, rope):
     assert not bool(K[:, :row0].any()) and not bool(K[:, row0 + rows:].any())
 
 
-ATTN_CASES = [  # H, dh, nq, Lkv, splits, gain
+ATTN_CASES = [  # H, dh, nq, Lkv, splits, gain (the last two: more splits than the combine kernel takes in one group,
+    # and more splits than key tiles, so some splits see no key at all)
     (2, 64, 70, 333, 1, 1.0), (3, 72, 200, 1000, 3, 1.0), (2, 128, 130, 515, 2, 1.0), (2, 40, 33, 120, 1, 1.0),
+    (2, 72, 100, 2100, 12, 4.0), (1, 64, 40, 700, 16, 1.0),
     (2, 72, 129, 4096, 4, 8.0), (1, 128, 64, 700, 5, 8.0), (4, 64, 256, 64, 1, 1.0), (2, 96, 31, 257, 1, 1.0),
 ]
 
