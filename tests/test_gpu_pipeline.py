@@ -120,3 +120,27 @@ def test_guided_sampling_loop_matches_oracle(name, S):
         assert e < tol * S
     finally:
         pipe.destroy()
+
+
+@pytest.mark.parametrize("i", list(range(10)))
+def test_sampling_loop_random_configurations(i):
+    """The sampling loop on drawn stage configurations (same generator as the random stage sweep), N = 2 or 3 stages,
+    two or three steps, the first one synchronous."""
+    from test_gpu_random_stages import _draw_config
+    from paper_2405_14430_amd.pipeline import Pipeline
+    cfg, _, rng = _draw_config(100 + i)
+    cfg = wl.variant(cfg, txt_pre_only_last=0)            # a per-stage property; the loop builds every stage from one cfg
+    N, S = int(rng.integers(2, 4)), int(rng.integers(2, 4))
+    _log("random pipeline", i, {k: cfg[k] for k in ("kind", "dtype", "n_layers", "hidden", "head_dim", "seq_img", "n_patches",
+                                                     "text_len", "qk_norm", "joint_rope")}, "N", N, "S", S)
+    W = wl.make_weights(cfg, n_layers=N * cfg["n_layers"])
+    A = wl.make_activations(cfg)
+    conds, dts = wl.make_sampling(cfg, S)
+    ref, trace = PipelineOracle(cfg, wl.split_stages(W, N)).run(A["x"], conds, dts, warmup_steps=1, text=A["text"])
+    pipe = Pipeline(cfg, wl.split_stages(W, N))
+    try:
+        x = pipe.run(_f32(A["x"]), [_f32(c) for c in conds], dts, warmup_steps=1, text=_text_dev(cfg, A))
+        torch.cuda.synchronize()
+        assert _relerr(x, ref) < TOL[cfg["dtype"]] * S
+    finally:
+        pipe.destroy()
