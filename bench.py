@@ -122,6 +122,24 @@ def main():
     tokens_per_s = n / (ms_per_step * 1e-3)
     tflops = call_flops(cfg, n) / (ms_per_step * 1e-3) / 1e12
 
+    # joint-attention kinds: the call that carries the text rows (patch 0 of a step) is heavier; time it too and give the
+    # aggregate of a whole step's M calls (one with text, M - 1 without)
+    joint_extra = None
+    if cfg["kind"] in (2, 3) and text is not None:
+        tout = torch.empty_like(text)
+        reps = max(4, min(args.steps, 40))
+        for _ in range(2):
+            st.patch_forward(xs[0], cond, 0, text=text, out=ys[0], text_out=tout)
+        torch.cuda.synchronize()
+        tt0 = time.perf_counter()
+        for _ in range(reps):
+            st.patch_forward(xs[0], cond, 0, text=text, out=ys[0], text_out=tout)
+        torch.cuda.synchronize()
+        ms_text = (time.perf_counter() - tt0) * 1e3 / reps
+        step_ms = ms_text + (M - 1) * ms_per_step
+        joint_extra = {"ms_call_with_text_rows": ms_text, "text_rows": cfg["text_len"],
+                       "ms_per_step_of_M_calls": step_ms, "tokens_per_s_over_step": M * n / (step_ms * 1e-3)}
+
     # second pass, same steps, with HIP event pairs around every launch on the stage's stream
     st.profile(1)
     for i in range(args.steps):
@@ -219,6 +237,8 @@ def main():
         "tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
+    if joint_extra:
+        out["joint_step"] = joint_extra
     print(json.dumps(out))
 
 
