@@ -196,10 +196,16 @@ def main():
         t = json.load(open(tpath)).get("kernels", {}).get(dom)
         if t:
             traffic = t["fetch_bytes"] + t["write_bytes"]
+    # measured ceiling of the matrix pipes (register-only MFMA loop), beside the data-sheet peak
+    mfma_loop = None
+    if cfg["dtype"] == "bf16":
+        from paper_2405_14430_amd import probe_mfma_tflops
+        mfma_loop = probe_mfma_tflops()
     roofline = {"kernel": dom, "classes": g["classes"], "bound": "mfma" if cfg["dtype"] == "bf16" else "alu",
                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
                 "avg_launch_us": g["ms"] / g["launches"] * 1e3, "launches_per_step": g["launches"],
-                "flops_per_launch": g["flops"] / g["launches"], "event_overhead_us": event_overhead_us}
+                "flops_per_launch": g["flops"] / g["launches"], "event_overhead_us": event_overhead_us,
+                "mfma_loop_tflops": mfma_loop, "frac_of_mfma_loop": (ach / mfma_loop) if mfma_loop else None}
 
     cpu = None
     if not args.no_cpu:

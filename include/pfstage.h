@@ -322,6 +322,15 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
                           void *out, int64_t ldo, int nq, int splits, void *ws, size_t ws_bytes,
                           void *stream);
 
+/*
+ * Measurement aid (no part of the method): enqueues a register-only loop of bf16 32x32x16 MFMAs - `workgroups` workgroups
+ * of four waves, `iters` x 32 MFMAs per wave - and stores the launch's flop count in *flops (host).  out: device float
+ * [workgroups * 256], overwritten.  Timed by the benchmark (events on `stream`) it gives the matrix rate the chip sustains
+ * at the clock it holds under such a load, the measured ceiling beside the data-sheet peak (Sec. 5 reports per-model
+ * rates only; the ceiling is this build's own yardstick).
+ */
+pf_status pf_probe_mfma_loop(float *out, int workgroups, int iters, double *flops, void *stream);
+
 /* Tuning hook for the bf16 GEMM: 0 = the library's own tile heuristic (default); other values pin one tile
  * configuration for every following launch of the process (used by the tile sweeps behind the heuristic).
  * Values 100 + v select the attention kernel generation instead (100 = default); 200 / 201 switch the fused K/V

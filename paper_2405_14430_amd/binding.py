@@ -54,7 +54,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_patch_forward", "pf_kv_view", "pf_xattn_kv_view", "pf_stage_attention_plan", "pf_stage_set_stream",
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
-           "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention", "pf_attention_kernel_name",
+           "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention", "pf_attention_kernel_name", "pf_probe_mfma_loop",
            "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
 
 _lib = None
@@ -111,6 +111,8 @@ def load_library():
     lib.pf_op_kv_scatter.argtypes = [i32, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, f32, vp]
     lib.pf_attention_kernel_name.restype = C.c_char_p
     lib.pf_attention_kernel_name.argtypes = [i32, i32, i32, i32, i32]
+    lib.pf_probe_mfma_loop.restype = i32
+    lib.pf_probe_mfma_loop.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
     lib.pf_op_attention_ws_bytes.restype = sz
     lib.pf_op_attention_ws_bytes.argtypes = [i32, i32, i32, i32]
     lib.pf_op_attention.restype = i32
@@ -338,6 +340,20 @@ def pf_op_attention(q, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, spl
     _ok(lib.pf_op_attention(_dt_code(q), path, _ptr(q), q.stride(0), _ptr(kbuf), _ptr(vtbuf), kv_rows, rows_padded,
                             n_heads, head_dim, _ptr(out), out.stride(0), nq, splits, _ptr(ws), wsb, _stream_ptr()))
     return out
+
+
+def probe_mfma_tflops(workgroups=512, iters=4000):
+    """TFLOP/s of a register-only bf16 MFMA loop on the current device and stream (measured ceiling of the matrix pipes)."""
+    lib = load_library()
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    fl = C.c_double()
+    _ok(lib.pf_probe_mfma_loop(_ptr(out), workgroups, 50, C.byref(fl), _stream_ptr()))      # warm-up
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _ok(lib.pf_probe_mfma_loop(_ptr(out), workgroups, iters, C.byref(fl), _stream_ptr()))
+    e1.record()
+    e1.synchronize()
+    return fl.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 def pf_op_axpy(x, y, alpha, out=None):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpfstage.so")
-SOURCES = ["elementwise.hip", "gemm_simt.hip", "gemm_mfma.hip", "gemm_mfma_dl.hip", "attn_simt.hip", "attn_mfma.hip", "attn_mfma2.hip", "stage.hip"]
+SOURCES = ["elementwise.hip", "gemm_simt.hip", "gemm_mfma.hip", "gemm_mfma_dl.hip", "attn_simt.hip", "attn_mfma.hip", "attn_mfma2.hip", "probe.hip", "stage.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 arithmetic is kept off for all device code

@@ -89,6 +89,7 @@ size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits);
 hipError_t launch_attention(const AttnArgs &a, hipStream_t s, bool *used_combine);
 
 hipError_t launch_axpby(const float *x, const float *y, float a, float b, float *out, int64_t n, hipStream_t s);
+hipError_t launch_mfma_loop(float *out, int workgroups, int iters, hipStream_t s);   // measurement aid (probe.hip)
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);   // bytes multiple of 16, p 16-byte aligned
 
 // kernel-path specific pieces (defined in gemm_*.hip / attn_*.hip)

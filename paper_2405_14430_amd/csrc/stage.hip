@@ -815,6 +815,13 @@ const char *pf_attention_kernel_name(int dtype, int path, int head_dim, int nq, 
   return name;
 }
 
+pf_status pf_probe_mfma_loop(float *out, int workgroups, int iters, double *flops, void *stream) {
+  if (!out || !flops) return PF_ERR_NULL;
+  if (workgroups < 1 || workgroups > 65536 || iters < 1) return PF_ERR_SHAPE;
+  *flops = (double)workgroups * 4.0 * (double)iters * 32.0 * 32768.0;
+  return launch_mfma_loop(out, workgroups, iters, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
 size_t pf_op_attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
   return attention_ws_bytes(nq, n_heads, head_dim, splits);
 }

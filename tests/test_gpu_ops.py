@@ -323,3 +323,10 @@ def test_op_argument_errors_do_not_launch():
     A = torch.zeros(8, 20, device="cuda")
     with pytest.raises(pkg.PfError):
         pkg.pf_op_gemm(A, A, None)                                       # K not a multiple of 8
+
+
+def test_mfma_loop_probe_reports_a_plausible_rate():
+    """The measurement aid behind bench.py's measured matrix ceiling: above the fp32 vector peak, below the sheet figure."""
+    tf = _pkg().probe_mfma_tflops(workgroups=512, iters=500)
+    _log("mfma loop", tf)
+    assert 300.0 < tf < 2600.0
