@@ -201,6 +201,17 @@ def main():
     if cfg["dtype"] == "bf16":
         from paper_2405_14430_amd import probe_mfma_tflops
         mfma_loop = probe_mfma_tflops()
+    # measured device-to-device copy rate (256 MiB, read + write bytes), the yardstick for the streaming kernels' GB/s
+    src_, dst_ = torch.empty(1 << 28, dtype=torch.uint8, device="cuda"), torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dst_.copy_(src_)
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ce0.record()
+    for _ in range(4):
+        dst_.copy_(src_)
+    ce1.record()
+    ce1.synchronize()
+    hbm_copy_gbs = 4 * 2 * (1 << 28) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del src_, dst_
     roofline = {"kernel": dom, "classes": g["classes"], "bound": "mfma" if cfg["dtype"] == "bf16" else "alu",
                 "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
                 "avg_launch_us": g["ms"] / g["launches"] * 1e3, "launches_per_step": g["launches"],
@@ -241,7 +252,7 @@ def main():
                    "seq_img": cfg["seq_img"], "n_patches": M, "patch_tokens": n, "kv_rows": wl.kv_rows(cfg),
                    "text_len": cfg["text_len"]},
         "tflops": tflops, "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "hbm_copy_gbs": hbm_copy_gbs,
     }
     if joint_extra:
         out["joint_step"] = joint_extra
