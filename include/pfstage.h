@@ -85,13 +85,13 @@ typedef struct {
   int32_t gelu_tanh;   /* 1: tanh form of GELU, 0: erf form */
   int32_t kernel_path; /* pf_kernel_path */
   int32_t batch;       /* B: images per call, 0 or 1 = one, at most PF_MAX_BATCH.  B = 2 is one image run with and
-                          without its condition for classifier-free guidance (Sec. 4.1.3 keeps the two on separate device
+                          without its condition for classifier-free guidance (Sec. 4.1, CFG parallel, keeps the two on separate device
                           groups; on one device they share the weights and every GEMM).  Each image has K/V buffers of its
                           own.  With B > 1 every per-call array gains a leading image axis: x_patch / y_patch [B, n, d],
                           x_prev / y_prev [B, L, d], cond [B, d or 6d], text / text_out [B, T, ...]. */
   int32_t qk_norm;     /* 1: q and k of every head are RMS-normalised over the head's channels (learned scale
                           q_norm_w / k_norm_w, eps = ln_eps) right after the projection and before any RoPE, as the
-                          Flux-family blocks do (the paper names the models, Sec. 5, not this detail).  head_dim must
+                          Flux-family blocks do (the paper names the models, Sec. 4, not this detail).  head_dim must
                           be a power of two.  0: off */
   int32_t joint_rope;  /* kind 2 only, 1: RoPE on q and k of the image rows exactly as in kind 3 (text rows are not
                           rotated): the two-stream block of Flux-like models.  0: off */
@@ -189,7 +189,8 @@ pf_status pf_stage_create(const pf_config *cfg, const pf_layer_weights *layers, 
 pf_status pf_kv_init(pf_stage *stage, const float *x_prev, const pf_cond *cond_prev, float *y_prev);
 
 /*
- * One pipeline micro-step of this stage on patch `patch_idx` (0 <= patch_idx < M):
+ * One pipeline micro-step (Sec. 3.3: one device works on one patch with its own layers; the example of micro-step 5 fixes
+ * which rows are fresh) of this stage on patch `patch_idx` (0 <= patch_idx < M):
  * x_patch float [n, d] device in, y_patch float [n, d] device out (may alias).  For every layer:
  * modulation, LayerNorm+modulate, QKV projection (RoPE for kind 3), write of the patch's K/V into buffer
  * rows [off, off+n) BEFORE attention (all other rows are left exactly as they are), attention of the
@@ -200,8 +201,9 @@ pf_status pf_stage_patch_forward(pf_stage *stage, const float *x_patch, const pf
                                  int patch_idx, float *y_patch);
 
 /*
- * Read-only view of one layer's buffer (borrowed pointers into kv_buffer, valid until destroy; contents
- * valid after a stream synchronise).  Element (row r, head h, channel c) of K lives at
+ * Read-only view of one layer's buffer: the K/V activations of the whole token sequence, which every device keeps for
+ * its own layers (Sec. 3.3; Sec. 3.4, Table 1: (1/N)(KV)L per device).  Borrowed pointers into kv_buffer, valid until
+ * destroy; contents valid after a stream synchronise.  Element (row r, head h, channel c) of K lives at
  *   (char*)k + elem_bytes * (r*k_row_stride + h*k_head_stride + c*k_col_stride), likewise for V.
  * Rows [0, text_rows) are the joint text rows (kinds 2, 3), rows [text_rows, rows) the image tokens.
  * K of kind 3 is stored after RoPE.  V is kept transposed (row stride 1) so that the attention kernel
@@ -326,20 +328,19 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
  * Measurement aid (no part of the method): enqueues a register-only loop of bf16 32x32x16 MFMAs - `workgroups` workgroups
  * of four waves, `iters` x 32 MFMAs per wave - and stores the launch's flop count in *flops (host).  out: device float
  * [workgroups * 256], overwritten.  Timed by the benchmark (events on `stream`) it gives the matrix rate the chip sustains
- * at the clock it holds under such a load, the measured ceiling beside the data-sheet peak (Sec. 5 reports per-model
- * rates only; the ceiling is this build's own yardstick).
+ * at the clock it holds under such a load: the measured ceiling beside the data-sheet peak, this library's own yardstick.
  */
 pf_status pf_probe_mfma_loop(float *out, int workgroups, int iters, double *flops, void *stream);
 
-/* Tuning hook for the bf16 GEMM: 0 = the library's own tile heuristic (default); other values pin one tile
- * configuration for every following launch of the process (used by the tile sweeps behind the heuristic).
- * Values 100 + v select the attention kernel generation instead (100 = default); 200 / 201 switch the fused K/V
- * routing of the QKV projection off / on; 300 + s pins the attention ring depth (300 = default); 400 + k sets the
- * smallest K (in units of 64) and 500 + t the largest tile count (in units of 16 tiles of 64 x 64) for which the
- * wave-split-K GEMM kernel is chosen (t < 100); 600 + s pins the key-split count of the stage's attention launches
- * (600 = heuristic; still capped at one split per four key tiles); 700 / 701 / 702: 256-query attention workgroups
- * by launch size / never / always; 800 / 801 switch the folding of the softmax exponent factor into q off / on. */
-void pf_tune_gemm_tile(int id);
+/* pf_op_gemm with the tile configuration of the bf16 MFMA kernel chosen by the caller for this one launch: tile = 0 lets
+ * the library's heuristic pick (then it is pf_op_gemm), 1 .. pf_gemm_tile_count() pins one of the configurations the
+ * heuristic chooses from (the unit tests run every one of them on ragged shapes).  Nothing outlives the call.  tile > 0
+ * needs dtype PF_BF16, path PF_PATH_AUTO and K a multiple of 64 (PF_ERR_SHAPE otherwise); tile out of range: PF_ERR_RANGE. */
+int pf_gemm_tile_count(void);
+pf_status pf_op_gemm_tile(int tile, int dtype, int path, const void *A, int64_t lda, const void *W, int64_t ldw,
+                          const void *bias, void *C, int64_t ldc, int M, int N, int K, int epilogue, int gelu_from,
+                          int gelu_tanh, const float *gate, const float *R, int64_t ldr, void *C2, int64_t ldc2,
+                          void *stream);
 
 #ifdef __cplusplus
 }

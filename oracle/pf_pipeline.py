@@ -111,7 +111,7 @@ def scheme_costs(scheme, p, hs, L, N, kv_bytes_per_layer, param_bytes):
 class CfgPipelineOracle:
     """Classifier-free guidance on top of the patch pipeline: every step runs the stage stack on the same latent with
     the conditional and the unconditional conditioning (two independent sets of K/V buffers, shared weights; the paper
-    runs the two on separate device groups, Sec. 4.1.3), combines eps = eps_u + scale * (eps_c - eps_u) and applies
+    runs the two on separate device groups, Sec. 4.1, CFG parallel), combines eps = eps_u + scale * (eps_c - eps_u) and applies
     the update."""
 
     def __init__(self, cfg, stage_layers):

@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("PFSTAGE_LIB") or os.path.join(_HERE, "libpfstage.so")   # override: another build of the library
+LIB_PATH = os.path.join(_HERE, "libpfstage.so")
 
 PF_F32, PF_BF16 = 0, 1
 PF_PATH_AUTO, PF_PATH_SIMT = 0, 1
@@ -55,7 +55,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention", "pf_attention_kernel_name", "pf_probe_mfma_loop",
-           "pf_tune_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
+           "pf_gemm_tile_count", "pf_op_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
 
 _lib = None
 
@@ -123,8 +123,10 @@ def load_library():
     lib.pf_op_axpy.argtypes = [vp, vp, f32, vp, i64, vp]
     lib.pf_op_axpby.restype = i32
     lib.pf_op_axpby.argtypes = [vp, vp, f32, f32, vp, i64, vp]
-    lib.pf_tune_gemm_tile.restype = None
-    lib.pf_tune_gemm_tile.argtypes = [i32]
+    lib.pf_gemm_tile_count.restype = i32
+    lib.pf_gemm_tile_count.argtypes = []
+    lib.pf_op_gemm_tile.restype = i32
+    lib.pf_op_gemm_tile.argtypes = [i32] + lib.pf_op_gemm.argtypes
     _lib = lib
     return lib
 
@@ -305,8 +307,9 @@ def pf_op_ln_modulate(x, shift, scale, eps, dtype, normalize=True):
 
 
 def pf_op_gemm(A, W, bias, epilogue=0, gelu_from=None, gelu_tanh=1, gate=None, R=None, want_copy=False,
-               path=PF_PATH_AUTO):
-    """epilogue 0 -> dtype [M,N]; epilogue 1 -> (float32 [M,N] new residual, optional dtype copy)."""
+               path=PF_PATH_AUTO, tile=0):
+    """epilogue 0 -> dtype [M,N]; epilogue 1 -> (float32 [M,N] new residual, optional dtype copy).
+    tile > 0 goes through pf_op_gemm_tile (one tile configuration of the bf16 kernel, this launch only)."""
     lib = load_library()
     M, K = A.shape
     N = W.shape[0]
@@ -316,10 +319,10 @@ def pf_op_gemm(A, W, bias, epilogue=0, gelu_from=None, gelu_tanh=1, gate=None, R
     else:
         Cc = torch.empty(M, N, dtype=torch.float32, device=A.device)
         C2 = torch.empty(M, N, dtype=A.dtype, device=A.device) if want_copy else None
-    _ok(lib.pf_op_gemm(_dt_code(A), path, _ptr(A), A.stride(0), _ptr(W), W.stride(0), _ptr(bias), _ptr(Cc),
-                       Cc.stride(0), M, N, K, epilogue, N if gelu_from is None else gelu_from, gelu_tanh, _ptr(gate),
-                       _ptr(R), 0 if R is None else R.stride(0), _ptr(C2), 0 if C2 is None else C2.stride(0),
-                       _stream_ptr()))
+    args = (_dt_code(A), path, _ptr(A), A.stride(0), _ptr(W), W.stride(0), _ptr(bias), _ptr(Cc),
+            Cc.stride(0), M, N, K, epilogue, N if gelu_from is None else gelu_from, gelu_tanh, _ptr(gate),
+            _ptr(R), 0 if R is None else R.stride(0), _ptr(C2), 0 if C2 is None else C2.stride(0), _stream_ptr())
+    _ok(lib.pf_op_gemm_tile(int(tile), *args) if tile else lib.pf_op_gemm(*args))
     return Cc if epilogue == 0 else (Cc, C2)
 
 

@@ -264,14 +264,8 @@ hipError_t attn_launch(const AttnArgs &a, hipStream_t s) {
   using C = AttnCfg<DH>;
   const int B = a.batch > 1 ? a.batch : 1;
   dim3 g((a.nq + TQ - 1) / TQ, a.n_heads * B, a.splits);
-  size_t smem = (size_t)(2 * C::K_ELEMS + 2 * C::V_ELEMS) * sizeof(bf16_t);
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<DH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr int smem = (2 * C::K_ELEMS + 2 * C::V_ELEMS) * (int)sizeof(bf16_t);
+  if (hipError_t e = allow_dynamic_lds<&attn_mfma_kernel<DH>, smem>(); e != hipSuccess) return e;
   attn_mfma_kernel<DH><<<g, 256, smem, s>>>((const bf16_t *)a.q, a.ldq, (const bf16_t *)a.kbuf,
                                             (const bf16_t *)a.vtbuf, a.kv_rows, a.rows_padded, a.n_heads * B, a.head_dim,
                                             (bf16_t *)a.out, a.ldo, a.nq, a.splits, a.ws, a.n_heads);

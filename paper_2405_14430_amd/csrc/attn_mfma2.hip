@@ -24,9 +24,6 @@
 
 namespace pf {
 
-int g_attn_stages = 0;   // tuning hook: 0 = default ring depth, 2 / 3 = forced
-int g_attn_wide = 0;     // tuning hook: 0 = 256-query workgroups when the launch has enough queries, 1 = never, 2 = always
-
 namespace {
 
 constexpr int TK = 64;
@@ -443,13 +440,7 @@ hipError_t launch2(const AttnArgs &a, hipStream_t s) {
   constexpr int TQ = C::TQ;
   static_assert(2 * C::LPS <= 63, "two tiles of loads must fit the vmcnt counter");
   constexpr int smem = NS * C::STAGE;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma2_kernel<DH, NS, PRE, NW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  if (hipError_t e = allow_dynamic_lds<&attn_mfma2_kernel<DH, NS, PRE, NW>, smem>(); e != hipSuccess) return e;
   const int qtiles = (a.nq + TQ - 1) / TQ;
   const int B = a.batch > 1 ? a.batch : 1;
   dim3 g(qtiles * a.n_heads * B * a.splits);

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace pf {
 
 typedef __bf16 bf16_t;
@@ -13,6 +15,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kWave = 64;
+
+// Raises a kernel's dynamic-LDS limit to Bytes, once per kernel instance and process, safely from any number of host
+// threads (stages on different threads share the kernels).  Every later call returns the first call's status.
+template <auto Kernel, int Bytes>
+inline hipError_t allow_dynamic_lds() {
+  static std::once_flag once;
+  static hipError_t status = hipSuccess;
+  std::call_once(once, [] {
+    status = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, Bytes);
+  });
+  return status;
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {

@@ -16,6 +16,8 @@
 //    chain of K iterations by four; the four partial tiles are then summed through LDS.
 // Both finish through LDS: the fp32 tile is laid out row-major and every thread applies the epilogue to runs of 8
 // consecutive columns (16-byte bf16 stores, 32-byte fp32 stores).
+#include <mutex>
+
 #include "common.h"
 #include "epilogue.h"
 #include "ops.h"
@@ -514,13 +516,7 @@ hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
   // the stage ring, or the fp32 tile (row stride BN + 4) that replaces it for the epilogue, whichever is larger
   constexpr int ring = NSTAGE * (BM + BN) * KB * 2, tile = BM * (BN + 4) * 4;
   constexpr int smem = (tile > ring && tile <= 96 * 1024) ? tile : ring;   // larger tiles finish in row passes
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  if (hipError_t e = allow_dynamic_lds<&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB>, smem>(); e != hipSuccess) return e;
   const int64_t T = (int64_t)((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
   dim3 g((unsigned)(((T + 7) / 8) * 8));
   gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
@@ -532,13 +528,7 @@ hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
 template <int BM, int BN>
 hipError_t launch_wavek(const GemmArgs &a, hipStream_t s) {
   constexpr int smem = 4 * 2 * (BM + BN) * ROW_BYTES;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_wavek_kernel<BM, BN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  if (hipError_t e = allow_dynamic_lds<&gemm_wavek_kernel<BM, BN>, smem>(); e != hipSuccess) return e;
   const int64_t T = (int64_t)((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
   dim3 g((unsigned)(((T + 7) / 8) * 8));
   gemm_wavek_kernel<BM, BN><<<g, 256, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N, a.K,
@@ -554,10 +544,6 @@ bool gemm_kv_route_supported(const GemmArgs &a) {
 }
 
 bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= BK && a.M >= 1 && a.N >= 1; }
-
-int g_gemm_tile_override = 0;   // tuning hook: 0 = heuristic, 1.. = a fixed tile configuration
-int g_wavek_min_k = 2048;       // tuning hook: smallest K the wave-split-K kernel takes
-int g_wavek_max_tiles = 512;    // tuning hook: it takes GEMMs with fewer 64 x 64 tiles than this
 
 // Tile heuristic, from A/B runs inside the stage on MI355X (weights come from HBM there, not from a warm L2, which
 // favours deeper rings than an isolated GEMM loop suggests):
@@ -599,41 +585,8 @@ static int pick_variant(const GemmArgs &a) {
   return V_64x64_S2;
 }
 
-hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
-  switch (g_gemm_tile_override) {
-    case 1: return launch_tile<256, 128, 3>(a, s);
-    case 2: return launch_tile<128, 128, 3>(a, s);
-    case 3: return launch_tile<128, 128, 2>(a, s);
-    case 4: return launch_tile<128, 64, 4>(a, s);
-    case 5: return launch_tile<64, 64, 4>(a, s);
-    case 6: return launch_tile<256, 128, 2>(a, s);
-    case 7: return launch_tile<128, 64, 2>(a, s);
-    case 8: return launch_tile<64, 64, 2>(a, s);
-    case 9: return launch_gemm_mfma(a, s);
-    case 10: return launch_wavek<64, 64>(a, s);
-    case 11: return launch_wavek<64, 32>(a, s);
-    case 12: return launch_wavek<32, 64>(a, s);
-    case 13: return launch_wavek<32, 32>(a, s);
-    case 14: return launch_tile<256, 128, 3, 4, 2>(a, s);
-    case 15: return launch_tile<256, 256, 2, 4, 2>(a, s);
-    case 16: return launch_tile<128, 256, 3, 2, 4>(a, s);
-    case 17: return launch_tile<256, 128, 2, 4, 2>(a, s);
-    case 18: return launch_tile<256, 256, 2, 2, 2>(a, s);
-    case 19: return launch_tile<128, 128, 2, 2, 2, 32>(a, s);
-    case 20: return launch_tile<128, 128, 3, 2, 2, 32>(a, s);
-    case 21: return launch_tile<128, 128, 4, 2, 2, 32>(a, s);
-    case 22: return launch_tile<256, 128, 3, 4, 2, 32>(a, s);
-    case 23: return launch_tile<256, 128, 4, 4, 2, 32>(a, s);
-    case 24: return launch_tile<256, 256, 3, 4, 2, 32>(a, s);
-    case 25: return launch_tile<256, 256, 4, 4, 2, 32>(a, s);
-    case 26: return launch_tile<64, 64, 3>(a, s);
-    case 27: return launch_tile<128, 64, 3>(a, s);
-    case 28: return launch_tile<128, 192, 2>(a, s);
-    case 29: return launch_tile<256, 192, 2, 4, 2>(a, s);
-    case 30: return launch_tile<128, 192, 3>(a, s);
-    default: break;
-  }
-  switch (pick_variant(a)) {
+static hipError_t launch_variant(int v, const GemmArgs &a, hipStream_t s) {
+  switch (v) {
     case V_256x256: return launch_tile<256, 256, 2, 4, 2>(a, s);
     case V_256x128_K32S3: return launch_tile<256, 128, 3, 4, 2, 32>(a, s);
     case V_256x128_S3: return launch_tile<256, 128, 3, 4, 2>(a, s);
@@ -649,6 +602,39 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
   }
 }
 
+int gemm_mfma_dl_tile_count() { return V_COUNT; }
+
+hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
+#ifdef PF_TUNING
+  // tile configurations outside the heuristic's set, for sweeps
+  switch (g_gemm_tile_override) {
+    case 1: return launch_tile<256, 128, 3>(a, s);
+    case 2: return launch_tile<128, 128, 3>(a, s);
+    case 3: return launch_tile<128, 128, 2>(a, s);
+    case 4: return launch_tile<128, 64, 4>(a, s);
+    case 5: return launch_tile<64, 64, 4>(a, s);
+    case 6: return launch_tile<256, 128, 2>(a, s);
+    case 7: return launch_tile<128, 64, 2>(a, s);
+    case 8: return launch_tile<64, 64, 2>(a, s);
+    case 9: return launch_gemm_mfma(a, s);
+    case 10: return launch_wavek<64, 64>(a, s);
+    case 14: return launch_tile<256, 128, 3, 4, 2>(a, s);
+    case 15: return launch_tile<256, 256, 2, 4, 2>(a, s);
+    case 16: return launch_tile<128, 256, 3, 2, 4>(a, s);
+    case 17: return launch_tile<256, 128, 2, 4, 2>(a, s);
+    case 22: return launch_tile<256, 128, 3, 4, 2, 32>(a, s);
+    case 26: return launch_tile<64, 64, 3>(a, s);
+    case 27: return launch_tile<128, 64, 3>(a, s);
+    case 28: return launch_tile<128, 192, 2>(a, s);
+    case 29: return launch_tile<256, 192, 2, 4, 2>(a, s);
+    case 30: return launch_tile<128, 192, 3>(a, s);
+    default: break;
+  }
+#endif
+  if (a.tile >= 1 && a.tile <= V_COUNT) return launch_variant(a.tile - 1, a, s);
+  return launch_variant(pick_variant(a), a, s);
+}
+
 const char *gemm_mfma_dl_variant_name(const GemmArgs &a) {
   static const char *names[V_COUNT] = {"gemm_tile_kernel<256,256,2,4,2,64>", "gemm_tile_kernel<256,128,3,4,2,32>",
                                        "gemm_tile_kernel<256,128,3,4,2,64>", "gemm_tile_kernel<128,128,2,2,2,64>",
@@ -656,7 +642,7 @@ const char *gemm_mfma_dl_variant_name(const GemmArgs &a) {
                                        "gemm_tile_kernel<64,64,4,2,2,64>", "gemm_tile_kernel<64,64,3,2,2,64>",
                                        "gemm_tile_kernel<64,64,2,2,2,64>", "gemm_tile_kernel<128,192,2,2,2,64>",
                                        "gemm_tile_kernel<256,192,2,4,2,64>", "gemm_tile_kernel<128,192,3,2,2,64>"};
-  return names[pick_variant(a)];
+  return names[(a.tile >= 1 && a.tile <= V_COUNT) ? a.tile - 1 : pick_variant(a)];
 }
 
 }  // namespace pf

@@ -13,6 +13,24 @@ enum { PATH_AUTO = 0, PATH_SIMT = 1 };
 
 inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
+// Launch-plan constants.  In the library as shipped they are compile-time constants: no process-wide state can change
+// the plan of a live stage.  A build with -DPF_TUNING (tile and split sweeps on the GPU, never the shipped library)
+// turns them into variables behind pf_tune(), declared in tuning.h.
+#ifdef PF_TUNING
+#define PF_PLAN_CONST(name, value) extern int name
+#else
+#define PF_PLAN_CONST(name, value) constexpr int name = value
+#endif
+PF_PLAN_CONST(g_attn_variant, 0);       // 0 = newest attention kernel that supports the shape, 1 = first-generation kernel
+PF_PLAN_CONST(g_attn_stages, 0);        // attention ring depth: 0 = default, 2 / 3 = forced (4-wave kernel)
+PF_PLAN_CONST(g_attn_wide, 0);          // 0 = 256-query workgroups when the launch has enough queries, 1 = never, 2 = always
+PF_PLAN_CONST(g_force_splits, 0);       // > 0 replaces the split heuristic's count (still capped by the key tiles)
+PF_PLAN_CONST(g_fuse_kv_route, 1);      // K/V written by the QKV GEMM epilogue (1) or by the scatter kernel (0)
+PF_PLAN_CONST(g_fold_q_scale, 1);       // q reaches the attention kernel with its exponent factor folded in
+PF_PLAN_CONST(g_gemm_tile_override, 0); // 0 = tile heuristic, else a fixed tile configuration for every launch
+PF_PLAN_CONST(g_wavek_min_k, 2048);     // smallest K the wave-split-K GEMM kernel takes
+PF_PLAN_CONST(g_wavek_max_tiles, 512);  // it takes GEMMs with fewer 64 x 64 tiles than this
+
 hipError_t launch_modulation(int dt, const void *w, const void *b, const float *c, float *mod, int out_dim,
                              int in_dim, int table_mode, hipStream_t s);
 
@@ -53,6 +71,7 @@ struct GemmArgs {
   const float *R; int64_t ldr;
   void *C2; int64_t ldc2;
   GemmArgsKv kvr;      // kbuf == nullptr: plain GEMM
+  int tile;            // 0: the tile heuristic picks; 1 .. gemm_mfma_dl_tile_count(): that tile configuration, this launch only
 };
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
 bool gemm_kv_route_supported(const GemmArgs &a);   // the fused QKV -> K/V^T write needs the vectorised bf16 epilogue
@@ -98,13 +117,12 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);
 bool gemm_mfma_dl_supported(const GemmArgs &a);            // direct-to-LDS multi-stage variant (K % 64 == 0)
 hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s);
 const char *gemm_mfma_dl_variant_name(const GemmArgs &a);   // kernel instance the tile heuristic picks for this shape
+int gemm_mfma_dl_tile_count();                              // tile configurations the heuristic chooses from
 hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
 bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS variant for head sizes 64 / 72 / 128
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s);
 int attn_mfma2_qtile(int nq);                              // queries per workgroup it will use for nq query rows per image
-extern int g_attn_variant;                                 // tuning hook: 0 = newest attention kernel that supports the shape
-extern int g_attn_stages, g_attn_wide;                     // tuning hooks of that kernel: ring depth, workgroup width
 bool attn_mfma2_takes_prescaled_q(int head_dim);           // its kernel for this head size has a prescaled-q variant
 hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s);   // picks between the two
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s);

@@ -14,10 +14,6 @@
 
 using namespace pf;
 
-static int g_fuse_kv_route = 1;   // tuning hook 200/201: K/V written by the QKV GEMM epilogue (1) or the scatter kernel (0)
-static int g_fold_q_scale = 1;    // tuning hook 800/801: q handed to the attention kernel with its exponent factor folded in
-namespace pf { extern int g_attn_variant; }
-
 namespace {
 
 thread_local std::string g_create_error;
@@ -93,7 +89,6 @@ int use_path(const pf_config *c) { return (c->dtype == PF_BF16 && c->kernel_path
 // a single workgroup (no second wave per SIMD to overlap with), and the combine pass that grows with the split count.
 // Measured on MI355X: Flux-scale patch (384 blocks) 4 splits 478 us vs 2 splits 503 us vs none 583 us; SD3-scale patch
 // (96 blocks) 5 splits 34 us vs 6 splits 38 us.
-int g_force_splits = 0;   // tuning hook: > 0 replaces the heuristic's split count (still capped by the key tiles)
 int choose_splits(int path, int nq, int H, int kv_rows, int head_dim) {
   const bool gen2 = path != PATH_SIMT && pf::g_attn_variant == 0 && (head_dim == 64 || head_dim == 72 || head_dim == 128);
   const int qtile = path == PATH_SIMT ? 64 : (gen2 ? attn_mfma2_qtile(nq) : 128);
@@ -751,10 +746,22 @@ pf_status pf_op_ln_modulate(int dtype, const float *x, int64_t ldx, const float 
   return launch_ln_modulate(dtype, x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 
+int pf_gemm_tile_count(void) { return gemm_mfma_dl_tile_count(); }
+
 pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void *W, int64_t ldw, const void *bias, void *C,
                      int64_t ldc, int M, int N, int K, int epilogue, int gelu_from, int gelu_tanh, const float *gate,
                      const float *R, int64_t ldr, void *C2, int64_t ldc2, void *stream) {
+  return pf_op_gemm_tile(0, dtype, path, A, lda, W, ldw, bias, C, ldc, M, N, K, epilogue, gelu_from, gelu_tanh, gate, R, ldr, C2,
+                         ldc2, stream);
+}
+
+pf_status pf_op_gemm_tile(int tile, int dtype, int path, const void *A, int64_t lda, const void *W, int64_t ldw,
+                          const void *bias, void *C, int64_t ldc, int M, int N, int K, int epilogue, int gelu_from,
+                          int gelu_tanh, const float *gate, const float *R, int64_t ldr, void *C2, int64_t ldc2,
+                          void *stream) {
   if (!A || !W || !C || (epilogue == 1 && !R)) return PF_ERR_NULL;
+  if (tile < 0 || tile > gemm_mfma_dl_tile_count()) return PF_ERR_RANGE;
+  if (tile > 0 && (dtype != PF_BF16 || path != PF_PATH_AUTO || K % 64)) return PF_ERR_SHAPE;   // tiles exist for the bf16 MFMA kernels
   if (!dt_ok(dtype)) return PF_ERR_DTYPE;
   if (M < 0 || N < 1 || K < 8 || K % 8 || lda < K || ldw < K || lda % 8 || ldw % 8 || ldc < N || !al16(A) || !al16(W)) return PF_ERR_SHAPE;
   if (epilogue != 0 && epilogue != 1) return PF_ERR_SHAPE;
@@ -764,6 +771,7 @@ pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void
   g.dt = dtype; g.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT;
   g.A = A; g.lda = lda; g.W = W; g.ldw = ldw; g.bias = bias; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
   g.epilogue = epilogue; g.gelu_from = gelu_from; g.gelu_tanh = gelu_tanh; g.gate = gate; g.R = R; g.ldr = ldr; g.C2 = C2; g.ldc2 = ldc2;
+  g.tile = tile;
   return launch_gemm(g, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 
@@ -848,21 +856,7 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
 
 }  // extern "C"
 
-namespace pf { extern int g_gemm_tile_override, g_wavek_min_k, g_wavek_max_tiles; }
-extern "C" void pf_tune_gemm_tile(int id) {
-  if (id >= 800) g_fold_q_scale = id - 800;
-  else if (id >= 700) pf::g_attn_wide = id - 700;
-  else if (id >= 600) g_force_splits = id - 600;
-  else if (id >= 500) pf::g_wavek_max_tiles = (id - 500) * 16;
-  else if (id >= 400) pf::g_wavek_min_k = (id - 400) * 64;
-  else if (id >= 300) pf::g_attn_stages = id - 300;
-  else if (id >= 200) g_fuse_kv_route = id - 200;
-  else if (id >= 100) pf::g_attn_variant = id - 100;
-  else pf::g_gemm_tile_override = id;
-}
-
 namespace pf {
-int g_attn_variant = 0;   // tuning hook: 0 = newest kernel that supports the shape, 1 = first-generation kernel
 hipError_t launch_attn_bf16(const AttnArgs &a, hipStream_t s) {
   return (g_attn_variant == 0 && attn_mfma2_supported(a)) ? launch_attn_mfma2(a, s) : launch_attn_mfma(a, s);
 }

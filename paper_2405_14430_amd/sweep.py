@@ -82,7 +82,7 @@ def sweep_patch_call(name, patches, iters, warmup):
 
 def sweep_batch(name, batches, iters, warmup):
     """Patch call of the workload at its own M for B images per call (B = 2: the conditional and unconditional image of
-    classifier-free guidance share one call, Sec. 4.1.3 runs them on separate device groups instead)."""
+    classifier-free guidance share one call, Sec. 4.1 (CFG parallel) runs them on separate device groups instead)."""
     import torch
     from . import Stage
     base = wl.CONFIGS[name]

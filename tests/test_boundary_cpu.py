@@ -189,3 +189,52 @@ def test_attention_partials_always_fit_the_reserved_workspace(lib, name):
             assert need.value <= have.value and splits.value >= 1, (nq, cross)
     assert lib.pf_stage_attention_plan(h, Lkv + 1, 0, C.byref(splits), C.byref(need), C.byref(have)) == -6
     lib.pf_stage_destroy(h)
+
+
+def test_stages_created_and_planned_on_two_threads_agree(lib):
+    """No process-wide state takes part in a stage's launch plan: stages built and queried concurrently on two host
+    threads (each stage used by its own thread only) report what a stage built alone reports."""
+    import threading
+
+    names = ["C2", "C3", "C4", "C5", "C2s", "C4s"]
+
+    def plans(name):
+        cfg = wl.CONFIGS[name]
+        st, h = _fake_stage(lib, cfg)
+        assert st == 0
+        out = [lib.pf_stage_workspace_bytes(C.byref(B.make_config(cfg)))]
+        splits, need, have = C.c_int(), C.c_size_t(), C.c_size_t()
+        for nq in (1, wl.patch_rows(cfg), wl.kv_rows(cfg)):
+            for cross in ([0, 1] if cfg["kind"] == 1 else [0]):
+                assert lib.pf_stage_attention_plan(h, nq, cross, C.byref(splits), C.byref(need), C.byref(have)) == 0
+                out.append((nq, cross, splits.value, need.value, have.value))
+        n, d = wl.patch_rows(cfg), cfg["hidden"]
+        out.append(lib.pf_gemm_kernel_name(1, 0, n, 3 * d, d))
+        out.append(lib.pf_attention_kernel_name(1, 0, cfg["head_dim"], n, 1))
+        lib.pf_stage_destroy(h)
+        return out
+
+    alone = {nm: plans(nm) for nm in names}
+    got = [dict(), dict()]
+
+    def worker(slot, order):
+        for _ in range(20):
+            for nm in order:
+                got[slot][nm] = plans(nm)
+
+    ts = [threading.Thread(target=worker, args=(0, names)), threading.Thread(target=worker, args=(1, names[::-1]))]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert got[0] == alone and got[1] == alone
+
+
+def test_gemm_tile_entry_checks_without_launching(lib):
+    p = C.c_void_p(0x100000)
+    n = lib.pf_gemm_tile_count()
+    assert n >= 1
+    args = (1, 0, p, 64, p, 64, None, p, 64, 4, 64, 64, 0, 64, 1, None, None, 0, None, 0, None)
+    assert lib.pf_op_gemm_tile(n + 1, *args) == -6 and lib.pf_op_gemm_tile(-1, *args) == -6
+    assert lib.pf_op_gemm_tile(1, 0, *args[1:]) == -3            # tiles exist for bf16 only
+    assert lib.pf_op_gemm_tile(1, 1, 0, p, 72, p, 72, None, p, 64, 4, 64, 72, 0, 64, 1, None, None, 0, None, 0, None) == -3

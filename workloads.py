@@ -6,8 +6,8 @@ the method's arithmetic and imports neither the CPU oracle nor the HIP binding;
 both are fed from here so that they see bit-identical inputs.
 
 The shapes stand in for the PixArt / SD3 / Flux.1 runs of the paper's
-evaluation (Sec. 5, Experiments): trained weights and prompts are replaced by
-Gaussians, and "the previous diffusion step's input" (Sec. 4, the stale
+evaluation (Sec. 4, Experiments): trained weights and prompts are replaced by
+Gaussians, and "the previous diffusion step's input" (Sec. 3.3, the stale
 activations of timestep T+1) by x + 0.05*N(0,1).
 """
 from __future__ import annotations
