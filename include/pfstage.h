@@ -325,6 +325,26 @@ pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const
                           void *stream);
 
 /*
+ * pf_op_attention for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and same results as
+ * pf_op_attention with the same `splits`; the split partial results go into an array that is part of the library's
+ * device image (PF_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of a workspace argument.  The
+ * call allocates and frees nothing and synchronises nothing; q, kbuf, vtbuf and out are the caller's, as before.
+ *   - pf_op_attention_ws_bytes(nq, n_heads, head_dim, splits) > PF_STATIC_SCRATCH_BYTES: PF_ERR_WORKSPACE, nothing is
+ *     launched, pf_last_error(NULL) says how many bytes were needed.  Other argument errors as pf_op_attention.
+ *   - All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU (different
+ *     streams, or several host threads) race on it.  Calls on one stream are ordered and safe.  Nothing in the array
+ *     needs clearing between calls: a call reads only what it wrote itself.
+ *   - The array's device address is looked up on the first call on each device (hipGetSymbolAddress), which is host
+ *     work only; a caller that captures a graph may want to make one plain call first.
+ */
+#define PF_STATIC_SCRATCH_BYTES (32u << 20)
+size_t pf_static_scratch_bytes(void);
+pf_status pf_op_attention_static(int dtype, int path, const void *q, int64_t ldq, const void *kbuf,
+                                 const void *vtbuf, int kv_rows, int rows_padded, int n_heads, int head_dim,
+                                 void *out, int64_t ldo, int nq, int splits, void *stream);
+
+/*
  * Measurement aid (no part of the method): enqueues a register-only loop of bf16 32x32x16 MFMAs - `workgroups` workgroups
  * of four waves, `iters` x 32 MFMAs per wave - and stores the launch's flop count in *flops (host).  out: device float
  * [workgroups * 256], overwritten.  Timed by the benchmark (events on `stream`) it gives the matrix rate the chip sustains

@@ -55,7 +55,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention", "pf_attention_kernel_name", "pf_probe_mfma_loop",
-           "pf_gemm_tile_count", "pf_op_gemm_tile", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
+           "pf_gemm_tile_count", "pf_op_gemm_tile", "pf_static_scratch_bytes", "pf_op_attention_static", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
 
 _lib = None
 
@@ -117,6 +117,10 @@ def load_library():
     lib.pf_op_attention_ws_bytes.argtypes = [i32, i32, i32, i32]
     lib.pf_op_attention.restype = i32
     lib.pf_op_attention.argtypes = [i32, i32, vp, i64, vp, vp, i32, i32, i32, i32, vp, i64, i32, i32, vp, sz, vp]
+    lib.pf_static_scratch_bytes.restype = sz
+    lib.pf_static_scratch_bytes.argtypes = []
+    lib.pf_op_attention_static.restype = i32
+    lib.pf_op_attention_static.argtypes = [i32, i32, vp, i64, vp, vp, i32, i32, i32, i32, vp, i64, i32, i32, vp]
     lib.pf_gemm_kernel_name.restype = C.c_char_p
     lib.pf_gemm_kernel_name.argtypes = [i32, i32, i32, i32, i32]
     lib.pf_op_axpy.restype = i32
@@ -342,6 +346,17 @@ def pf_op_attention(q, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, spl
     ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=q.device)
     _ok(lib.pf_op_attention(_dt_code(q), path, _ptr(q), q.stride(0), _ptr(kbuf), _ptr(vtbuf), kv_rows, rows_padded,
                             n_heads, head_dim, _ptr(out), out.stride(0), nq, splits, _ptr(ws), wsb, _stream_ptr()))
+    return out
+
+
+def pf_op_attention_static(q, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, out, splits=1, path=PF_PATH_AUTO):
+    """pf_op_attention through the entry point that allocates nothing: `out` is the caller's, the split partials go into
+    the library's static scratch array."""
+    lib = load_library()
+    st = lib.pf_op_attention_static(_dt_code(q), path, _ptr(q), q.stride(0), _ptr(kbuf), _ptr(vtbuf), kv_rows, rows_padded,
+                                    n_heads, head_dim, _ptr(out), out.stride(0), q.shape[0], splits, _stream_ptr())
+    if st != 0:
+        raise PfError(st, lib.pf_last_error(None).decode())
     return out
 
 

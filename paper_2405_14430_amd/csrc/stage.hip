@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -834,24 +835,87 @@ size_t pf_op_attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
   return attention_ws_bytes(nq, n_heads, head_dim, splits);
 }
 
-pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const void *kbuf, const void *vtbuf, int kv_rows,
-                          int rows_padded, int n_heads, int head_dim, void *out, int64_t ldo, int nq, int splits, void *ws,
-                          size_t ws_bytes, void *stream) {
+static pf_status attention_args_check(int dtype, const void *q, int64_t ldq, const void *kbuf, const void *vtbuf, int kv_rows,
+                                      int rows_padded, int n_heads, int head_dim, const void *out, int64_t ldo, int nq,
+                                      int splits) {
   if (!q || !kbuf || !vtbuf || !out) return PF_ERR_NULL;
   if (!dt_ok(dtype)) return PF_ERR_DTYPE;
   const int64_t d = (int64_t)n_heads * head_dim;
   if (n_heads < 1 || head_dim < 8 || head_dim % 8 || head_dim > 128 || kv_rows < 1 || rows_padded % 128 || kv_rows > rows_padded ||
       ldq < d || ldo < d || ldq % 8 || ldo % 4 || nq < 0 || splits < 1 || splits > 64 || !al16(q) || !al16(kbuf) || !al16(vtbuf) || ((uintptr_t)out & 7))
     return PF_ERR_SHAPE;
-  if (splits > 1 && (!ws || ws_bytes < attention_ws_bytes(nq, n_heads, head_dim, splits) || !al16(ws))) return PF_ERR_WORKSPACE;
+  return PF_OK;
+}
+
+static pf_status attention_launch(int dtype, int path, const void *q, int64_t ldq, const void *kbuf, const void *vtbuf,
+                                  int kv_rows, int rows_padded, int n_heads, int head_dim, void *out, int64_t ldo, int nq,
+                                  int splits, float *ws, hipStream_t st) {
   AttnArgs a{};
   a.dt = dtype; a.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT;
   a.q = q; a.ldq = ldq; a.kbuf = kbuf; a.vtbuf = vtbuf; a.kv_rows = kv_rows; a.rows_padded = rows_padded; a.n_heads = n_heads;
-  a.head_dim = head_dim; a.out = out; a.ldo = ldo; a.nq = nq; a.splits = splits; a.ws = (float *)ws;
-  hipStream_t st = (hipStream_t)stream;
+  a.head_dim = head_dim; a.out = out; a.ldo = ldo; a.nq = nq; a.splits = splits; a.ws = ws;
   hipError_t e = a.path == PATH_SIMT ? launch_attn_simt(a, st) : launch_attn_bf16(a, st);
   if (e == hipSuccess && splits > 1) e = launch_attn_combine(a, st);
   return e == hipSuccess ? PF_OK : PF_ERR_DEVICE;
+}
+
+pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const void *kbuf, const void *vtbuf, int kv_rows,
+                          int rows_padded, int n_heads, int head_dim, void *out, int64_t ldo, int nq, int splits, void *ws,
+                          size_t ws_bytes, void *stream) {
+  pf_status st = attention_args_check(dtype, q, ldq, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, out, ldo, nq, splits);
+  if (st != PF_OK) return st;
+  if (splits > 1 && (!ws || ws_bytes < attention_ws_bytes(nq, n_heads, head_dim, splits) || !al16(ws))) return PF_ERR_WORKSPACE;
+  return attention_launch(dtype, path, q, ldq, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, out, ldo, nq, splits,
+                          (float *)ws, (hipStream_t)stream);
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------------------
+// Split-KV partial results of pf_op_attention_static live in this array instead of a caller-provided workspace.  Every
+// GPU the library runs on holds its own copy at its own address for the life of the process; host code never uses the
+// array's name as an address, only the per-device pointer that hipGetSymbolAddress returned.
+static __device__ __align__(256) unsigned char scratch[PF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` per device ordinal, filled on first use
+
+// Device address of this device's copy of `scratch` (the current device's; looked up once per device).
+pf_status static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PF_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PF_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PF_OK;
+}
+}  // namespace
+
+size_t pf_static_scratch_bytes(void) { return PF_STATIC_SCRATCH_BYTES; }
+
+pf_status pf_op_attention_static(int dtype, int path, const void *q, int64_t ldq, const void *kbuf, const void *vtbuf,
+                                 int kv_rows, int rows_padded, int n_heads, int head_dim, void *out, int64_t ldo, int nq,
+                                 int splits, void *stream) {
+  pf_status st = attention_args_check(dtype, q, ldq, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, out, ldo, nq, splits);
+  if (st != PF_OK) return st;
+  const size_t need = attention_ws_bytes(nq, n_heads, head_dim, splits);
+  if (need > PF_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, PF_ERR_WORKSPACE,
+                "pf_op_attention_static: the split partial results need " + std::to_string(need) + " bytes, the static scratch array holds " +
+                    std::to_string((size_t)PF_STATIC_SCRATCH_BYTES) + "; use fewer splits or query rows, or pf_op_attention with a workspace");
+  void *ws = nullptr;
+  if (splits > 1) {
+    st = static_scratch(&ws);
+    if (st != PF_OK) return fail(nullptr, st, "pf_op_attention_static: no device address for the static scratch array");
+  }
+  // Nothing in the array has to start at zero: the attention launch writes every (split, query, head) slot that the
+  // combine launch of the same call reads, so an earlier call's leftovers are never read.
+  return attention_launch(dtype, path, q, ldq, kbuf, vtbuf, kv_rows, rows_padded, n_heads, head_dim, out, ldo, nq, splits,
+                          (float *)ws, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -238,3 +238,17 @@ def test_gemm_tile_entry_checks_without_launching(lib):
     assert lib.pf_op_gemm_tile(n + 1, *args) == -6 and lib.pf_op_gemm_tile(-1, *args) == -6
     assert lib.pf_op_gemm_tile(1, 0, *args[1:]) == -3            # tiles exist for bf16 only
     assert lib.pf_op_gemm_tile(1, 1, 0, p, 72, p, 72, None, p, 64, 4, 64, 72, 0, 64, 1, None, None, 0, None, 0, None) == -3
+
+
+def test_static_scratch_entry_rejects_oversize_before_touching_the_device(lib):
+    """The entry point that allocates nothing has a fixed array for its split partials: a launch that needs more is
+    refused on the host, before any device call, with a message that names the sizes."""
+    p = C.c_void_p(0x100000)
+    cap = lib.pf_static_scratch_bytes()
+    assert cap == 32 << 20
+    assert lib.pf_op_attention_ws_bytes(4096, 16, 72, 8) > cap
+    assert lib.pf_op_attention_static(1, 0, p, 1152, p, p, 4096, 4096, 16, 72, p, 1152, 4096, 8, None) == -7
+    msg = lib.pf_last_error(None)
+    assert b"static scratch" in msg and str(cap).encode() in msg
+    assert lib.pf_op_attention_static(1, 0, p, 1152, p, p, 0, 4096, 16, 72, p, 1152, 64, 2, None) == -3     # no key rows
+    assert lib.pf_op_attention_static(1, 0, None, 1152, p, p, 128, 128, 16, 72, p, 1152, 64, 2, None) == -1
