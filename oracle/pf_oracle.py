@@ -87,10 +87,12 @@ def softmax_rows(s):
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention(q, k, v, n_heads, return_probs=False):
+def attention(q, k, v, n_heads, return_probs=False, weight_round=None):
     """Multi-head attention of queries q [nq, d] over keys/values k, v [nk, d].
 
     Head h owns columns [h*dh, (h+1)*dh).  Scores are scaled by 1/sqrt(dh).
+    weight_round: None (exact), or the storage-rounding probe of StageOracle applied to the softmax weights
+    before they multiply v.
     """
     q, k, v = (np.asarray(t, F64) for t in (q, k, v))
     nq, d = q.shape
@@ -100,6 +102,8 @@ def attention(q, k, v, n_heads, return_probs=False):
     for h in range(n_heads):
         sl = slice(h * dh, (h + 1) * dh)
         p = softmax_rows((q[:, sl] @ k[:, sl].T) / math.sqrt(dh))
+        if weight_round is not None:
+            p = weight_round(p)
         out[:, sl] = p @ v[:, sl]
         if return_probs:
             probs.append(p)
@@ -164,10 +168,23 @@ class StageOracle:
 
     Buffer rows: joint-attention kinds store the T text rows first, then the L
     image rows; the other kinds store the L image rows only.
+
+    storage_round: None for the oracle proper (exact float64 everywhere).  A test
+    may pass a function (e.g. round-to-nearest-even to bf16): it is then applied
+    to every intermediate tensor that a reduced-precision implementation keeps
+    in its storage type between two contractions - the normalised and modulated
+    rows, q / k / v (after norm and RoPE), the softmax weights, the attention
+    output, the GELU output, and for kind 1 the cross-attention's input copy,
+    queries, text keys / values and output - and to nothing else (residual
+    stream, modulation vectors, statistics and accumulations stay exact).  This
+    measures what the storage format alone costs; it is a probe for tolerance
+    tests, not a second definition of the stage.
     """
 
-    def __init__(self, cfg, layers):
+    def __init__(self, cfg, layers, storage_round=None):
         self.cfg = dict(cfg)
+        self._sr = storage_round
+        self.on_layer = None           # optional callback(layer index) after each block: progress lines of long runs
         self.kind = int(cfg["kind"])
         self.layers = [self._as64(w) for w in layers]
         self.nl = len(self.layers)
@@ -193,6 +210,10 @@ class StageOracle:
         self.kc = [None] * self.nl     # kind 1: text keys / values of the cross-attention
         self.vc = [None] * self.nl
         self.ready = False
+
+    def _st(self, t):
+        """Storage-rounding probe (identity for the oracle proper)."""
+        return t if self._sr is None else np.asarray(self._sr(t), F64)
 
     @staticmethod
     def _as64(w):
@@ -237,26 +258,29 @@ class StageOracle:
                 rows = x if xt is None else np.concatenate([xt, x], axis=0)
                 nt = 0 if xt is None else xt.shape[0]
                 sh, sc, g = self.modulation(w, cond)
-                h = ln_modulate(rows, sh, sc, self.eps)
+                h = self._st(ln_modulate(rows, sh, sc, self.eps))
                 qkv = linear(h, w["w_qkv"], w["b_qkv"])
                 q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
                 if self.qk_norm:
                     q = rms_norm_heads(q, w["q_norm_w"], H, self.eps)
                     k = rms_norm_heads(k, w["k_norm_w"], H, self.eps)
-                q = self._rope(q, img_tokens)
-                k = self._rope(k, img_tokens)
+                q = self._st(self._rope(q, img_tokens))
+                k = self._st(self._rope(k, img_tokens))
+                v = self._st(v)
                 if nt:
                     self.kbuf[l][:nt] = k[:nt]
                     self.vbuf[l][:nt] = v[:nt]
                 self.kbuf[l][row0:row0 + n] = k[nt:]
                 self.vbuf[l][row0:row0 + n] = v[nt:]
-                a = attention(q, self.kbuf[l], self.vbuf[l], H)
-                m = gelu(linear(h, w["w_up"], w["b_up"]), self.gelu_tanh)
+                a = self._st(attention(q, self.kbuf[l], self.vbuf[l], H, weight_round=self._sr))
+                m = self._st(gelu(linear(h, w["w_up"], w["b_up"]), self.gelu_tanh))
                 rows = rows + g * linear(np.concatenate([a, m], axis=1), w["w_down"], w["b_down"])
                 if nt:
                     xt, x = rows[:nt], rows[nt:]
                 else:
                     x = rows
+                if self.on_layer:
+                    self.on_layer(l)
                 continue
 
             # ---- kinds 0, 1, 2: sequential attention then MLP
@@ -268,7 +292,7 @@ class StageOracle:
             for si, (xs, ws) in enumerate(streams):
                 mod = self.modulation(ws, cond)
                 mods.append(mod)
-                h = ln_modulate(xs, mod[0], mod[1], self.eps)
+                h = self._st(ln_modulate(xs, mod[0], mod[1], self.eps))
                 qkv = linear(h, ws["w_qkv"], ws["b_qkv"])
                 q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
                 is_text = (len(streams) == 2 and si == 0)
@@ -278,6 +302,7 @@ class StageOracle:
                 if self.joint_rope and not is_text:      # text rows sit at grid position (0, 0): no rotation
                     q = self._rope(q, img_tokens)
                     k = self._rope(k, img_tokens)
+                q, k, v = self._st(q), self._st(k), self._st(v)
                 if is_text:
                     self.kbuf[l][: xs.shape[0]] = k
                     self.vbuf[l][: xs.shape[0]] = v
@@ -286,7 +311,7 @@ class StageOracle:
                     self.vbuf[l][row0:row0 + n] = v
                 if not (pre_only and is_text):
                     qs.append(q)
-            a_all = attention(np.concatenate(qs, axis=0), self.kbuf[l], self.vbuf[l], H)
+            a_all = self._st(attention(np.concatenate(qs, axis=0), self.kbuf[l], self.vbuf[l], H, weight_round=self._sr))
             new, r = [], 0
             for si, ((xs, ws), mod) in enumerate(zip(streams, mods)):
                 if pre_only and len(streams) == 2 and si == 0:
@@ -296,17 +321,19 @@ class StageOracle:
                 r += xs.shape[0]
                 xs = xs + mod[2] * linear(a, ws["w_o"], ws["b_o"])
                 if kind == KIND_ADALN_SINGLE_XATTN:
-                    qc = linear(xs, ws["xattn_wq"], ws["xattn_bq"])
-                    ac = attention(qc, self.kc[l], self.vc[l], H)
+                    qc = self._st(linear(self._st(xs), ws["xattn_wq"], ws["xattn_bq"]))
+                    ac = self._st(attention(qc, self.kc[l], self.vc[l], H, weight_round=self._sr))
                     xs = xs + linear(ac, ws["xattn_wo"], ws["xattn_bo"])
-                h2 = ln_modulate(xs, mod[3], mod[4], self.eps)
-                u = gelu(linear(h2, ws["w_up"], ws["b_up"]), self.gelu_tanh)
+                h2 = self._st(ln_modulate(xs, mod[3], mod[4], self.eps))
+                u = self._st(gelu(linear(h2, ws["w_up"], ws["b_up"]), self.gelu_tanh))
                 xs = xs + mod[5] * linear(u, ws["w_down"], ws["b_down"])
                 new.append(xs)
             if len(new) == 2:
                 xt, x = new
             else:
                 x = new[0]
+            if self.on_layer:
+                self.on_layer(l)
         return x, xt
 
     # -- warm-up / initialisation of the stale buffers ---------------------------
@@ -318,7 +345,7 @@ class StageOracle:
             if text is None:
                 raise ValueError("kind 1 needs the text features at kv_init")
             for l, w in enumerate(self.layers):
-                kv = linear(text, w["xattn_wkv"], w["xattn_bkv"])
+                kv = self._st(linear(text, w["xattn_wkv"], w["xattn_bkv"]))
                 self.kc[l], self.vc[l] = kv[:, :self.d], kv[:, self.d:]
         if x_prev is None:
             for l in range(self.nl):

@@ -28,9 +28,7 @@ def _cfg(**kw):
     c = dict(_BASE)
     c.update(kw)
     if c["cond_std"] is None:
-        # fp32 workloads: conditioning embedding N(0,1).  bf16 workloads: N(0, 0.5^2), which with N(0,0.02)
-        # modulation weights gives shift/scale/gate vectors of std 0.1-0.2, the range of trained adaLN blocks.
-        c["cond_std"] = 1.0 if c["dtype"] == "f32" else 0.5
+        c["cond_std"] = 1.0       # conditioning embedding N(0,1) unless the workload says otherwise (C4 does)
     assert c["hidden"] == c["n_heads"] * c["head_dim"]
     assert c["seq_img"] == c["grid_h"] * c["grid_w"]
     assert c["seq_img"] % c["n_patches"] == 0
@@ -43,12 +41,17 @@ CONFIGS = {
                seq_img=256, grid_h=16, grid_w=16, n_patches=4, w_std="fan_in", seed=0),
     "C2": _cfg(kind=1, dtype="bf16", n_layers=4, hidden=1152, n_heads=16, head_dim=72, mlp_dim=4608,
                seq_img=4096, grid_h=64, grid_w=64, n_patches=8, text_len=120, cross_dim=1152, seed=1),
+    # C3 and C5 draw the conditioning embedding at std 0.5, C4 at 0.25: the largest of {1, 0.5, 0.25} at which the bf16
+    # STORAGE of the matrix operands alone (all arithmetic exact) costs at most two thirds of the 2e-2 parity bar on
+    # the workload's own full-size call (tests/golden/bf16_floor.txt has the floors, tests/test_bf16_floor.py ties
+    # these values to them).  On the 7-layer Flux-scale stage the format alone exceeds the bar at std 0.5 and 1: the
+    # N(0,0.02) modulation weights at hidden 3072 turn a unit-variance embedding into gates of std 0.6.
     "C3": _cfg(kind=2, dtype="bf16", n_layers=3, hidden=1536, n_heads=24, head_dim=64, mlp_dim=6144,
-               seq_img=4096, grid_h=64, grid_w=64, n_patches=8, text_len=154, seed=2),
+               seq_img=4096, grid_h=64, grid_w=64, n_patches=8, text_len=154, seed=2, cond_std=0.5),
     "C4": _cfg(kind=3, dtype="bf16", n_layers=7, hidden=3072, n_heads=24, head_dim=128, mlp_dim=12288,
-               seq_img=16384, grid_h=128, grid_w=128, n_patches=8, text_len=512, seed=3),
+               seq_img=16384, grid_h=128, grid_w=128, n_patches=8, text_len=512, seed=3, cond_std=0.25),
     "C5": _cfg(kind=1, dtype="bf16", n_layers=4, hidden=1152, n_heads=16, head_dim=72, mlp_dim=4608,
-               seq_img=65536, grid_h=256, grid_w=256, n_patches=16, text_len=120, cross_dim=1152, seed=4),
+               seq_img=65536, grid_h=256, grid_w=256, n_patches=16, text_len=120, cross_dim=1152, seed=4, cond_std=0.5),
     # structural twins: same block kinds and head sizes, small enough for a full
     # oracle sweep in seconds, with ragged row counts (text lengths and patch
     # sizes that are not multiples of any kernel tile).
