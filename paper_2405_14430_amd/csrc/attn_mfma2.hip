@@ -10,7 +10,7 @@
 // so the online-softmax statistics are in-lane reductions plus one exchange with lane^32 and the O^T rescale is per lane.
 //
 // K tiles ([64 kv][dh], contiguous in the head-major buffer) and V^T tiles ([dh][64 kv]) come in with
-// global_load_lds_dwordx4 into a two- or three-stage LDS ring (one s_barrier per tile, the next one or two tiles in flight
+// global_load_lds_dwordx4 into a two- to four-stage LDS ring (one s_barrier per tile, the next one or two tiles in flight
 // during tile t).  The LDS side of those loads is lane-linear, so bank conflicts are handled by XOR-swizzling the 16-byte chunks of a
 // row (the loading lane fetches the chunk that belongs at its LDS slot); dh = 72 rows are 144 bytes, which is conflict
 // free without a swizzle.  Before the PV product the two half-waves exchange half of their packed P registers
@@ -54,7 +54,10 @@ struct Cfg {
   static constexpr int V_BYTES = V_ROWS * 128;
   static constexpr int V_INSTR = DH / 8;                 // 8 rows of 128 B per instruction
   static constexpr int STAGE = K_BYTES + V_BYTES;
-  static constexpr int LK = (K_INSTR + NW - 1) / NW, LV = (V_INSTR + NW - 1) / NW;   // instructions per wave
+  // Waves that issue the tile loads: all four of the 4-wave kernel; in the 8-wave kernel only waves 0..3, which reach the
+  // tile's barrier with time to spare (waves 4..7 are the critical path of a tile and issue none).
+  static constexpr int NWL = NW == 8 ? 4 : NW;
+  static constexpr int LK = (K_INSTR + NWL - 1) / NWL, LV = (V_INSTR + NWL - 1) / NWL;   // instructions per loading wave
   static constexpr int LPS = LK + LV;
   // Head sizes that leave padding rows in the V^T tile (72 -> 96 rows) get the softmax denominator for free: padding
   // row DH holds ones, so row DH of O^T accumulates sum_j P[j][q] in the matrix pipe (with the same rescaling as the
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   unsigned char *kdst[C::LK];
 #pragma unroll
   for (int i = 0; i < C::LK; ++i) {
-    int ins = min(i * NW + wave, C::K_INSTR - 1);         // surplus slots repeat the last instruction (same data)
+    int ins = min(i * C::NWL + (wave & (C::NWL - 1)), C::K_INSTR - 1);   // surplus slots repeat the last instruction (same data)
     int off = ins * 1024 + lane * 16;
     int r = off / C::KROW, p = (off % C::KROW) >> 4;
     koff[i] = r * C::KROW + ((p ^ C::kkey(r)) << 4);
@@ -127,12 +130,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   unsigned char *vdst[C::LV];
 #pragma unroll
   for (int i = 0; i < C::LV; ++i) {
-    int ins = min(i * NW + wave, C::V_INSTR - 1);
+    int ins = min(i * C::NWL + (wave & (C::NWL - 1)), C::V_INSTR - 1);
     int r = ins * 8 + (lane >> 3), p = lane & 7;
     voff[i] = (int64_t)r * Lp + ((p ^ ((r >> 1) & 7)) << 3);
     vdst[i] = smem + C::K_BYTES + ins * 1024;
   }
-  auto issue = [&](int stage, int t) {
+  auto issue = [&](int stage, int t) __attribute__((always_inline)) {
     const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
     const bf16_t *vsrc = vh + (size_t)t * TK;
 #pragma unroll
@@ -141,9 +144,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     for (int i = 0; i < C::LV; ++i) lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
   };
   // tiles in flight ahead of the one being worked on: NS - 1, or NS - 2 for the 8-wave schedule (see its loop)
+  const bool loader = wave < C::NWL;
 #pragma unroll
   for (int i = 0; i < (NW == 8 ? NS - 2 : NS - 1); ++i)
-    if (t_begin + i < t_end) issue(i, t_begin + i);
+    if (loader && t_begin + i < t_end) issue(i, t_begin + i);
 
   // ---- Q fragments (B operand): lane holds query q0 + l32, channels ks*16 + 8*hi .. +7
   bf16x8 qf[C::KS16];
@@ -197,27 +201,46 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
 
   bf16x8 pf[2][2];   // P^T fragments of the tile whose PV product comes next
-  // ---- S^T = K . Q^T, online softmax and the P^T fragments of tile t (K from `stage`)
-  auto qk_softmax = [&](int t, auto stage_c) {
+  f32x16 sacc[2];    // S^T of the tile whose softmax comes next (two blocks of 32 kv rows)
+  // The K and V^T fragments of the matrix phases are read from LDS PD instructions ahead of the MFMA that uses them
+  // (a ring of PD + 1 fragments in registers, the order pinned with scheduling barriers): a wave that is alone in its
+  // matrix phase - the other wave of its SIMD being in its softmax - would otherwise wait out an LDS round trip in front
+  // of every MFMA.
+  constexpr int PD = 3;
+  // ---- S^T = K . Q^T for the two 32-row blocks of a tile (K from `stage`); consecutive MFMAs alternate between the blocks
+  auto scores = [&](auto stage_c) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
-    // ---- S^T = K . Q^T for the two 32-row blocks of the tile
-    f32x16 sacc[2];
+    constexpr int NF = 2 * C::KS16;
+    auto kread = [&](int i) __attribute__((always_inline)) {
+      return *reinterpret_cast<const bf16x8 *>(kaddr[i >> 1] + (stage * C::STAGE + (i & 1) * 32 * C::KROW));
+    };
+    bf16x8 ring[PD + 1];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int i = 0; i < PD; ++i) ring[i] = kread(i);
+    if constexpr (!PRE) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+      for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
-      for (int ks = 0; ks < C::KS16; ++ks) {
-        bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kaddr[ks] + (stage * C::STAGE + b * 32 * C::KROW));
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], (PRE && ks == 0) ? cneg : sacc[b], 0, 0, 0);
-      }
-      if constexpr (C::TAIL8) {
-        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(ktail_addr + (stage * C::STAGE + b * 32 * C::KROW));
-        sacc[b] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, kf4),
-                                                           __builtin_bit_cast(short4v, qtail), sacc[b], 0, 0, 0);
+        for (int r = 0; r < 16; ++r) sacc[b2][r] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      if (i + PD < NF) ring[(i + PD) % (PD + 1)] = kread(i + PD);
+      __builtin_amdgcn_sched_barrier(0);
+      const int b2 = i & 1, ks = i >> 1;
+      sacc[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % (PD + 1)], qf[ks], (PRE && ks == 0) ? cneg : sacc[b2], 0, 0, 0);
+    }
+    if constexpr (C::TAIL8) {
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(ktail_addr + (stage * C::STAGE + b2 * 32 * C::KROW));
+        sacc[b2] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, kf4),
+                                                            __builtin_bit_cast(short4v, qtail), sacc[b2], 0, 0, 0);
       }
     }
-    // ---- online softmax on raw scores (the positive scale commutes with max)
+  };
+  // ---- online softmax of tile t on the raw scores in sacc (the positive scale commutes with max) and its P^T fragments
+  auto softmax = [&](int t) __attribute__((always_inline)) {
     if ((t + 1) * TK > kv_rows) {
       const int jbase = t * TK + 4 * hi;
 #pragma unroll
@@ -302,22 +325,27 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         pf[b][s2] = __builtin_bit_cast(bf16x8, u);
       }
   };
-  // ---- O^T += V^T . P^T with the V^T tile of `stage` and the fragments qk_softmax left
-  auto pv = [&](auto stage_c) {
+  // ---- O^T += V^T . P^T with the V^T tile of `stage` and the fragments softmax left; consecutive MFMAs go to different
+  // 32-channel blocks of O^T
+  auto pv = [&](auto stage_c) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
+    constexpr int NF = 4 * C::CB;
+    auto vread = [&](int i) __attribute__((always_inline)) {
+      return *reinterpret_cast<const bf16x8 *>(vaddr[i / C::CB] + (stage * C::STAGE + (i % C::CB) * 32 * 128));
+    };
+    bf16x8 ring[PD + 1];
 #pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb) {
+    for (int i = 0; i < PD; ++i) ring[i] = vread(i);
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vaddr[2 * b + s2] + (stage * C::STAGE + cb * 32 * 128));
-          oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[b][s2], oacc[cb], 0, 0, 0);
-        }
+    for (int i = 0; i < NF; ++i) {
+      if (i + PD < NF) ring[(i + PD) % (PD + 1)] = vread(i + PD);
+      __builtin_amdgcn_sched_barrier(0);
+      const int j = i / C::CB, cb = i % C::CB;
+      oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % (PD + 1)], pf[j >> 1][j & 1], oacc[cb], 0, 0, 0);
     }
   };
   if constexpr (NW == 4) {
-  auto tile_step = [&](int t, auto stage_c) {
+  auto tile_step = [&](int t, auto stage_c) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     // tile t has landed once at most min(NS-2, tiles left after t) later tiles of this wave are still in flight
     if (NS >= 4 && t + 2 < t_end) wait_vmcnt<(NS >= 4 ? 2 * C::LPS : 0)>();
@@ -327,7 +355,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     asm volatile("" ::: "memory");
     if (t + NS - 1 < t_end) issue((stage + NS - 1) % NS, t + NS - 1);
 
-    qk_softmax(t, stage_c);
+    scores(stage_c);
+    softmax(t);
     pv(stage_c);
   };
   for (int t = t_begin; t < t_end; t += NS) {
@@ -341,25 +370,43 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     }
   }
   } else {
-    // 8 waves, two per SIMD, one barrier per tile for all of them.  Waves 4..7 run the tile body rotated: PV of the
-    // previous tile, then S and softmax of this one, so that on every SIMD one wave is in its softmax (VALU) while the
-    // other is in a matrix phase.  The previous tile's V^T stage therefore stays live one step longer and the prefetch
-    // distance is NS - 2 tiles: at step t the loads of tile t + NS - 2 go into the stage tile t - 2 used.
+    // 8 waves, two per SIMD (waves w and w + 4), one barrier per tile for all of them.  A wave's tile is a matrix phase
+    // (PV of the previous tile, then S of this one: 32 MFMAs) and a vector phase (softmax: exponentials, conversions).
+    // The two waves of a SIMD run them in opposite order, so that after every barrier one is in its matrix phase while
+    // the other is in its vector phase and they swap half a tile later:
+    //   waves 0..3:  PV(t-1), S(t)   | softmax(t)
+    //   waves 4..7:  softmax(t-1)    | PV(t-1), S(t)
+    // Either way the previous tile's V^T stage stays live one step longer, so the prefetch distance is NS - 2 tiles:
+    // at step t the loads of tile t + NS - 2 go into the stage tile t - 2 used.
     static_assert(NW == 4 || NS == 4, "the 8-wave schedule is written for a four-stage ring");
-    const bool rot = wave >= 4;
+    const bool late = wave >= 4;
     // (the two schedules are separate loops so that neither pays for the other's live registers)
-    auto top = [&](int t, auto stage_c) {
+    // Waves 0..3 load: they wait for their own loads of tile t before the barrier, so that behind the barrier the tile is
+    // complete for every wave, and issue the loads of tile t + NS - 2 after it.  Waves 4..7 only meet the barrier.
+    auto top = [&](int t, auto stage_c) __attribute__((always_inline)) {
       constexpr int stage = decltype(stage_c)::value;
-      if (t + 1 < t_end) wait_vmcnt<C::LPS>(); else wait_vmcnt<0>();   // tile t landed; tile t + 1 may be in flight
+      if (!late) {
+        if (t + 1 < t_end) wait_vmcnt<C::LPS>(); else wait_vmcnt<0>();   // tile t landed; tile t + 1 may be in flight
+      }
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (t + NS - 2 < t_end) issue((stage + NS - 2) % NS, t + NS - 2);
+      if (!late && t + NS - 2 < t_end) issue((stage + NS - 2) % NS, t + NS - 2);
     };
-    if (!rot) {
-      auto step = [&](int t, auto stage_c) {
+    auto pv_last = [&]() __attribute__((always_inline)) {
+      switch ((t_end - 1 - t_begin) % NS) {
+        case 0: pv(std::integral_constant<int, 0>{}); break;
+        case 1: pv(std::integral_constant<int, 1>{}); break;
+        case 2: pv(std::integral_constant<int, 2>{}); break;
+        default: pv(std::integral_constant<int, 3 % NS>{}); break;
+      }
+    };
+    if (!late) {
+      auto step = [&](int t, auto stage_c) __attribute__((always_inline)) {
+        constexpr int stage = decltype(stage_c)::value;
         top(t, stage_c);
-        qk_softmax(t, stage_c);
-        pv(stage_c);
+        if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+        scores(stage_c);
+        softmax(t);
       };
       for (int t = t_begin; t < t_end; t += NS) {
         step(t, std::integral_constant<int, 0>{});
@@ -367,12 +414,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
         if (t + 3 < t_end) step(t + 3, std::integral_constant<int, 3>{});
       }
+      if (t_end > t_begin) pv_last();
     } else {
-      auto step = [&](int t, auto stage_c) {
+      auto step = [&](int t, auto stage_c) __attribute__((always_inline)) {
         constexpr int stage = decltype(stage_c)::value;
         top(t, stage_c);
-        if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
-        qk_softmax(t, stage_c);
+        if (t > t_begin) {
+          softmax(t - 1);
+          pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+        }
+        scores(stage_c);
       };
       for (int t = t_begin; t < t_end; t += NS) {
         step(t, std::integral_constant<int, 0>{});
@@ -381,12 +432,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         if (t + 3 < t_end) step(t + 3, std::integral_constant<int, 3>{});
       }
       if (t_end > t_begin) {
-        switch ((t_end - 1 - t_begin) % NS) {
-          case 0: pv(std::integral_constant<int, 0>{}); break;
-          case 1: pv(std::integral_constant<int, 1>{}); break;
-          case 2: pv(std::integral_constant<int, 2>{}); break;
-          default: pv(std::integral_constant<int, 3 % NS>{}); break;
-        }
+        softmax(t_end - 1);
+        pv_last();
       }
     }
   }

@@ -97,55 +97,72 @@ hipError_t launch_modulation(int dt, const void *w, const void *b, const float *
 }
 
 // ------------------------------------------------------------------------------------------------
-// LayerNorm + modulate: one wave per row, the row lives in registers (single pass over HBM).
-// NC = float4 chunks per lane; d <= NC * 256.
+// LayerNorm + modulate: WPR waves per row (1, 2 or 4), the row lives in registers (single pass over HBM).  One wave
+// per row when there are rows enough to fill the chip with memory requests; fewer rows (a patch of 512 or 2048 tokens
+// is only that many waves) are split over two or four waves each, which exchange their partial sums through LDS.
+// NC = float4 chunks per lane; d <= NC * 256 * WPR.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int NC>
+template <typename T, int NC, int WPR>
 __global__ __launch_bounds__(256) void ln_modulate_kernel(const float *__restrict__ x, int64_t ldx,
                                                           const float *__restrict__ shift,
                                                           const float *__restrict__ scale, float eps,
                                                           T *__restrict__ out, int64_t ldo, int rows, int d,
                                                           int normalize, int seg_rows, int64_t seg_stride) {
   // rows are image-major, seg_rows per image; image b uses shift + b * seg_stride, scale + b * seg_stride
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  if (seg_rows > 0) {
+  constexpr int RPB = 4 / WPR;                       // rows per block
+  __shared__ float part[2][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wir = wave % WPR;                        // this wave's index inside its row
+  const int row = blockIdx.x * RPB + wave / WPR;
+  const bool live = row < rows;                      // (waves of a dead row still meet the barriers)
+  if (live && seg_rows > 0) {
     const int64_t o = (int64_t)(row / seg_rows) * seg_stride;
     shift += o;
     scale += o;
   }
-  const float *xr = x + (size_t)row * ldx;
+  const float *xr = x + (size_t)(live ? row : 0) * ldx;
   float4 v[NC];
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
-    int c = (lane + 64 * i) * 4;
-    if (c < d) {
+    int c = ((i * WPR + wir) * 64 + lane) * 4;
+    if (live && c < d) {
       v[i] = *reinterpret_cast<const float4 *>(xr + c);
       sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
     } else {
       v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
+  // sum over the row: within the wave, then over the row's WPR waves (fixed order: the result does not depend on timing)
+  auto row_sum = [&](float s, int slot) -> float {
+    s = wave_sum(s);
+    if constexpr (WPR == 1) return s;
+    if (lane == 0) part[slot][wave] = s;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < WPR; ++w) t += part[slot][(wave / WPR) * WPR + w];
+    return t;
+  };
   float mean = 0.f, rstd = 1.f;
   if (normalize) {
-    mean = wave_sum(sum) / (float)d;
+    mean = row_sum(sum, 0) / (float)d;
     float sq = 0.f;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-      int c = (lane + 64 * i) * 4;
+      int c = ((i * WPR + wir) * 64 + lane) * 4;
       if (c < d) {
         float a = v[i].x - mean, b = v[i].y - mean, e = v[i].z - mean, f = v[i].w - mean;
         sq += (a * a + b * b) + (e * e + f * f);
       }
     }
-    rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+    rstd = rsqrtf(row_sum(sq, 1) / (float)d + eps);
   }
+  if (!live) return;
   T *orow = out + (size_t)row * ldo;
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
-    int c = (lane + 64 * i) * 4;
+    int c = ((i * WPR + wir) * 64 + lane) * 4;
     if (c < d) {
       float y[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
       if (normalize) {
@@ -167,23 +184,36 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float *__restric
   }
 }
 
-template <typename T, int NC>
+template <typename T, int NC, int WPR>
 static void ln_launch(const float *x, int64_t ldx, const float *shift, const float *scale, float eps, void *out,
                       int64_t ldo, int rows, int d, int normalize, int seg_rows, int64_t seg_stride, hipStream_t s) {
-  ln_modulate_kernel<T, NC><<<dim3((rows + 3) / 4), 256, 0, s>>>(x, ldx, shift, scale, eps, (T *)out, ldo, rows, d,
-                                                                normalize, seg_rows, seg_stride);
+  constexpr int RPB = 4 / WPR;
+  ln_modulate_kernel<T, NC, WPR><<<dim3((rows + RPB - 1) / RPB), 256, 0, s>>>(x, ldx, shift, scale, eps, (T *)out, ldo, rows, d,
+                                                                          normalize, seg_rows, seg_stride);
+}
+
+template <typename T, int WPR>
+static hipError_t ln_dispatch_wpr(const float *x, int64_t ldx, const float *shift, const float *scale, float eps,
+                                  void *out, int64_t ldo, int rows, int d, int normalize, int seg_rows, int64_t seg_stride,
+                                  hipStream_t s) {
+  int need = (d + 256 * WPR - 1) / (256 * WPR);
+#define PF_LN_CASE(NC) \
+  if (need <= NC) { ln_launch<T, NC, WPR>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s); return hipGetLastError(); }
+  PF_LN_CASE(1) PF_LN_CASE(2) PF_LN_CASE(3) PF_LN_CASE(4) PF_LN_CASE(5) PF_LN_CASE(6) PF_LN_CASE(8) PF_LN_CASE(12) PF_LN_CASE(16) PF_LN_CASE(32)
+#undef PF_LN_CASE
+  return hipErrorInvalidValue;  // d > 8192 is rejected by the caller
 }
 
 template <typename T>
 static hipError_t ln_dispatch(const float *x, int64_t ldx, const float *shift, const float *scale, float eps,
                               void *out, int64_t ldo, int rows, int d, int normalize, int seg_rows, int64_t seg_stride,
                               hipStream_t s) {
-  int need = (d + 255) / 256;
-#define PF_LN_CASE(NC) \
-  if (need <= NC) { ln_launch<T, NC>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s); return hipGetLastError(); }
-  PF_LN_CASE(2) PF_LN_CASE(4) PF_LN_CASE(5) PF_LN_CASE(6) PF_LN_CASE(8) PF_LN_CASE(12) PF_LN_CASE(16) PF_LN_CASE(32)
-#undef PF_LN_CASE
-  return hipErrorInvalidValue;  // d > 8192 is rejected by the caller
+  // one wave per row needs about 8192 rows to keep every CU busy with memory requests (32 waves per CU); below that
+  // the rows are split (a row of fewer than 512 floats is not worth splitting)
+  const int wpr = (rows >= 8192 || d < 512) ? 1 : ((rows >= 4096 || d < 1024) ? 2 : 4);
+  if (wpr == 4) return ln_dispatch_wpr<T, 4>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s);
+  if (wpr == 2) return ln_dispatch_wpr<T, 2>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s);
+  return ln_dispatch_wpr<T, 1>(x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, seg_rows, seg_stride, s);
 }
 
 hipError_t launch_ln_modulate(int dt, const float *x, int64_t ldx, const float *shift, const float *scale,

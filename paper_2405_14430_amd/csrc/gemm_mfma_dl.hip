@@ -17,6 +17,7 @@
 // Both finish through LDS: the fp32 tile is laid out row-major and every thread applies the epilogue to runs of 8
 // consecutive columns (16-byte bf16 stores, 32-byte fp32 stores).
 #include <mutex>
+#include <type_traits>
 
 #include "common.h"
 #include "epilogue.h"
@@ -49,6 +50,15 @@ __device__ __forceinline__ void wait_tiles_behind(int behind) {
 __device__ __forceinline__ void lds_load16(const bf16_t *g, unsigned char *lds_wave_uniform) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
                                    (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void unrolled(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    unrolled<N, I + 1>(f);
+  }
 }
 
 // Workgroup id -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2; giving every
@@ -232,7 +242,7 @@ __device__ __forceinline__ void tile_epilogue(const float *tile, int m0, int n0,
 // ------------------------------------------------------------------------------------------------------------------
 // WGM x WGN wavefronts on one shared tile
 // ------------------------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2, int KB = 64>
+template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2, int KB = 64, bool SPREAD_LOADS = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t *__restrict__ A, int64_t lda,
                                                         const bf16_t *__restrict__ W, int64_t ldw, int M, int N, int K,
                                                         Epilogue<bf16_t> epi, int vec_ok, int n_major) {
@@ -281,6 +291,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
 #pragma unroll
     for (int i = 0; i < LW; ++i) lds_load16(pw[i] + koff, sw + (i * NW + wave) * 1024);
   };
+  // load instruction `idx` (A instructions first, then W) of this wave for K tile kt
+  auto issue_one = [&](auto idx_c, int stage, int kt) __attribute__((always_inline)) {
+    constexpr int idx = decltype(idx_c)::value;
+    unsigned char *sa = smem + stage * STAGE_BYTES;
+    if constexpr (idx < LA) lds_load16(pa[idx] + kt * KB, sa + (idx * NW + wave) * 1024);
+    else lds_load16(pw[idx - LA] + kt * KB, sa + BM * RBY + ((idx - LA) * NW + wave) * 1024);
+  };
 
   // small tiles: the epilogue's residual / gate operands are requested first, ahead of every tile load
   constexpr bool EPRE = BM * BN / 8 / (64 * NW) <= 2;
@@ -315,18 +332,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
     wkey[j] = key(r);
   }
 
+  // SPREAD: the loads of the tile that is prefetched during K tile kt are not issued in one burst after the barrier but
+  // one at a time between the MFMA groups of the tile (the burst fills the memory pipeline's queue and every wave
+  // then stalls at its own load instructions before it can start on its MFMAs).  Every iteration issues the same LPS
+  // loads - past the last K tile it repeats the last tile into the stage that has just been freed - so the loop body has
+  // no branch around a load and the wait in front of tile kt is the same for every kt.
+  constexpr int KS = KB / 16;
+  constexpr bool SPREAD = SPREAD_LOADS && MI * NI * KS >= 2 * LPS;
+  const int prologue_tiles = min(NSTAGE - 1, nk);
   for (int kt = 0; kt < nk; ++kt) {
     // tiles still in flight behind tile kt: min(NSTAGE-2, nk-1-kt); wait until only their loads are outstanding
-    const int behind = min(NSTAGE - 2, nk - 1 - kt);
+    const int behind = SPREAD ? prologue_tiles - 1 : min(NSTAGE - 2, nk - 1 - kt);
     wait_tiles_behind<LPS, NSTAGE - 2>(behind);
     // plain s_barrier: __syncthreads() would also drain every global load in flight (vmcnt(0)), i.e. the prefetches
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + NSTAGE - 1 < nk) issue((kt + NSTAGE - 1) % NSTAGE, kt + NSTAGE - 1);
+    const int ld_stage = (kt + NSTAGE - 1) % NSTAGE, ld_kt = min(kt + NSTAGE - 1, nk - 1);
+    if constexpr (!SPREAD) {
+      if (kt + NSTAGE - 1 < nk) issue(ld_stage, kt + NSTAGE - 1);
+    }
     const unsigned char *st = smem + (kt % NSTAGE) * STAGE_BYTES;
     // Fragments are read from LDS PRE k-steps ahead of the MFMAs that use them: with one accumulator per wave
     // (64x64 tile) a k-step is a single MFMA, far shorter than an LDS read, so the whole tile is preloaded.
-    constexpr int KS = KB / 16;
     constexpr int PRE = (MI * NI <= 2) ? KS : 2;
     bf16x8 af[PRE][MI], wf[PRE][NI];
     auto lread = [&](int buf, int ks) {
@@ -338,18 +365,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_tile_kernel(const bf16_t 
     };
 #pragma unroll
     for (int ks = 0; ks < PRE - 1; ++ks) lread(ks, ks);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    unrolled<KS>([&](auto ks_c) __attribute__((always_inline)) {
+      constexpr int ks = decltype(ks_c)::value;
       if (ks + PRE - 1 < KS) lread((ks + PRE - 1) % PRE, ks + PRE - 1);
       // keep the LDS reads of the next k-step ahead of this k-step's MFMAs (the scheduler would otherwise sink them
       // to reuse the fragment registers, exposing the LDS latency at every k-step)
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks % PRE][i], wf[ks % PRE][j], acc[i][j], 0, 0, 0);
-    }
+      unrolled<MI * NI>([&](auto m_c) __attribute__((always_inline)) {
+        constexpr int m = decltype(m_c)::value, i = m / NI, j = m % NI;
+        if constexpr (SPREAD) {
+          // MFMA number g of the tile's G = MI * NI * KS; load l goes in front of MFMA (2 l + 1) G / (2 LPS)
+          constexpr int g = ks * MI * NI + m, G = MI * NI * KS;
+          constexpr int l = g * LPS / G;
+          if constexpr (l < LPS && g == ((2 * l + 1) * G) / (2 * LPS)) {
+            issue_one(std::integral_constant<int, l>{}, ld_stage, ld_kt);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks % PRE][i], wf[ks % PRE][j], acc[i][j], 0, 0, 0);
+      });
+    });
   }
 
   // accumulators -> row-major fp32 tile in LDS (lane -> column l32, register r -> row 8*(r/4) + 4*hi + r%4), in
@@ -511,15 +546,15 @@ bool vec_epilogue_ok(const GemmArgs &a) {
   return ok;
 }
 
-template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2, int KB = 64>
+template <int BM, int BN, int NSTAGE, int WGM = 2, int WGN = 2, int KB = 64, bool SPREAD = false>
 hipError_t launch_tile(const GemmArgs &a, hipStream_t s) {
   // the stage ring, or the fp32 tile (row stride BN + 4) that replaces it for the epilogue, whichever is larger
   constexpr int ring = NSTAGE * (BM + BN) * KB * 2, tile = BM * (BN + 4) * 4;
   constexpr int smem = (tile > ring && tile <= 96 * 1024) ? tile : ring;   // larger tiles finish in row passes
-  if (hipError_t e = allow_dynamic_lds<&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB>, smem>(); e != hipSuccess) return e;
+  if (hipError_t e = allow_dynamic_lds<&gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB, SPREAD>, smem>(); e != hipSuccess) return e;
   const int64_t T = (int64_t)((a.N + BN - 1) / BN) * ((a.M + BM - 1) / BM);
   dim3 g((unsigned)(((T + 7) / 8) * 8));
-  gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
+  gemm_tile_kernel<BM, BN, NSTAGE, WGM, WGN, KB, SPREAD><<<g, 64 * WGM * WGN, smem, s>>>((const bf16_t *)a.A, a.lda, (const bf16_t *)a.W, a.ldw, a.M, a.N,
                                                        a.K, make_epilogue<bf16_t>(a), vec_epilogue_ok(a) ? 1 : 0,
                                                        a.N >= a.M ? 1 : 0);
   return hipGetLastError();
@@ -557,6 +592,12 @@ bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= 
 //    rounds, which power-of-two tiles cannot do for widths that are multiples of 3 * 1024 (Flux-scale stage, patch of
 //    2048 rows: QKV 171 -> 144 us with 768 tiles of 128x192, MLP-up 178 -> 172 us with 512 tiles of 256x192, MLP-down
 //    241 -> 214 us with 256 tiles of 128x192 and three stages); not for K = 1152, where the two-stage ring is exposed.
+//  * the three-stage 128x192 tile (long K, few tiles) issues its prefetch loads one at a time between the MFMAs of the
+//    tile instead of in a burst after the barrier (isolated GEMM, interleaved A/B rounds: 2048x3072x15360 204 -> 183 us,
+//    4096x1152x4608 65 -> 55 us; inside the Flux-scale stage 225 -> 193 us).  The other tiles keep the burst: the
+//    two-stage 128x192 tile gains alone (2048x9216x3072 129 -> 122 us) but not inside the stage (150 -> 154 us), the
+//    8-wave tiles and the 64x64 tiles lose (256x192: 152 -> 171 us, 256x256 at 8192^3: 995 -> 1063 us, 64x64: 15.2 ->
+//    17.7 us).
 enum { V_256x256 = 0, V_256x128_K32S3, V_256x128_S3, V_128x128, V_128x64, V_WAVEK, V_64x64_S4, V_64x64_S3, V_64x64_S2,
        V_128x192_S2, V_256x192_S2, V_128x192_S3, V_COUNT };
 
@@ -597,7 +638,7 @@ static hipError_t launch_variant(int v, const GemmArgs &a, hipStream_t s) {
     case V_64x64_S3: return launch_tile<64, 64, 3>(a, s);
     case V_128x192_S2: return launch_tile<128, 192, 2>(a, s);
     case V_256x192_S2: return launch_tile<256, 192, 2, 4, 2>(a, s);
-    case V_128x192_S3: return launch_tile<128, 192, 3>(a, s);
+    case V_128x192_S3: return launch_tile<128, 192, 3, 2, 2, 64, true>(a, s);
     default: return launch_tile<64, 64, 2>(a, s);
   }
 }
@@ -628,6 +669,19 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
     case 28: return launch_tile<128, 192, 2>(a, s);
     case 29: return launch_tile<256, 192, 2, 4, 2>(a, s);
     case 30: return launch_tile<128, 192, 3>(a, s);
+    case 40: return launch_tile<128, 192, 2, 2, 2, 64, true>(a, s);
+    case 41: return launch_tile<256, 192, 2, 4, 2, 64, true>(a, s);
+    case 42: return launch_tile<128, 192, 3, 2, 2, 64, true>(a, s);
+    case 43: return launch_tile<256, 256, 2, 4, 2, 64, true>(a, s);
+    case 44: return launch_tile<256, 128, 3, 4, 2, 64, true>(a, s);
+    case 45: return launch_tile<128, 128, 2, 2, 2, 64, true>(a, s);
+    case 46: return launch_tile<128, 192, 4, 2, 2, 64, true>(a, s);
+    case 47: return launch_tile<128, 128, 3, 2, 2, 64, true>(a, s);
+    case 48: return launch_tile<128, 128, 4, 2, 2, 64, true>(a, s);
+    case 49: return launch_tile<128, 64, 4, 2, 2, 64, true>(a, s);
+    case 50: return launch_tile<64, 64, 4, 2, 2, 64, true>(a, s);
+    case 51: return launch_tile<128, 256, 3, 2, 2, 64, true>(a, s);
+    case 52: return launch_tile<128, 192, 3, 2, 2, 64, false>(a, s);
     default: break;
   }
 #endif
@@ -636,12 +690,12 @@ hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s) {
 }
 
 const char *gemm_mfma_dl_variant_name(const GemmArgs &a) {
-  static const char *names[V_COUNT] = {"gemm_tile_kernel<256,256,2,4,2,64>", "gemm_tile_kernel<256,128,3,4,2,32>",
-                                       "gemm_tile_kernel<256,128,3,4,2,64>", "gemm_tile_kernel<128,128,2,2,2,64>",
-                                       "gemm_tile_kernel<128,64,2,2,2,64>", "gemm_wavek_kernel<64,64>",
-                                       "gemm_tile_kernel<64,64,4,2,2,64>", "gemm_tile_kernel<64,64,3,2,2,64>",
-                                       "gemm_tile_kernel<64,64,2,2,2,64>", "gemm_tile_kernel<128,192,2,2,2,64>",
-                                       "gemm_tile_kernel<256,192,2,4,2,64>", "gemm_tile_kernel<128,192,3,2,2,64>"};
+  static const char *names[V_COUNT] = {"gemm_tile_kernel<256,256,2,4,2,64,false>", "gemm_tile_kernel<256,128,3,4,2,32,false>",
+                                       "gemm_tile_kernel<256,128,3,4,2,64,false>", "gemm_tile_kernel<128,128,2,2,2,64,false>",
+                                       "gemm_tile_kernel<128,64,2,2,2,64,false>", "gemm_wavek_kernel<64,64>",
+                                       "gemm_tile_kernel<64,64,4,2,2,64,false>", "gemm_tile_kernel<64,64,3,2,2,64,false>",
+                                       "gemm_tile_kernel<64,64,2,2,2,64,false>", "gemm_tile_kernel<128,192,2,2,2,64,false>",
+                                       "gemm_tile_kernel<256,192,2,4,2,64,false>", "gemm_tile_kernel<128,192,3,2,2,64,true>"};
   return names[(a.tile >= 1 && a.tile <= V_COUNT) ? a.tile - 1 : pick_variant(a)];
 }
 
