@@ -193,6 +193,35 @@ def test_cost_table_relations_and_library_buffer_size():
     assert stage_bytes - cross == pf_["kv_bytes"]   # 4096 rows need no padding
 
 
+def test_cost_table_against_the_printed_table_and_the_n_below_2l_statement():
+    """Every entry of scheme_costs against the table as the paper prints it (tests/golden/parallel_schemes.txt), and
+    against the one consequence the paper states in numbers: PipeFusion communicates least exactly as long as N < 2L
+    (Sec. 3.4) - a wrong constant in its entry or in SP-Ulysses's, the closest competitor, moves that threshold."""
+    rows = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "parallel_schemes.txt")):
+        f = line.split()
+        if f and not line.startswith("#"):
+            rows[f[0]] = f[1:]
+    assert set(rows) == {"tensor_parallel", "distrifusion", "sp_ring", "sp_ulysses", "pipefusion"}
+    p, hs, P, KV = 4096, 1152, 6.0e8, 3.0e7
+    for L in (4, 28, 38):                     # 38: the layer count the paper quotes for Stable-Diffusion-3
+        for N in (1, 2, 4, 8, 2 * L - 1, 2 * L, 2 * L + 1, 5 * L):
+            env = {"L": float(L), "N": float(N)}
+            got = {k: pp.scheme_costs(k, p, hs, L, N, KV, P) for k in rows}
+            for k, (comm, ov, mem, kv) in rows.items():
+                assert got[k]["comm_elements"] == pytest.approx(eval(comm, {}, env) * p * hs), (k, L, N)
+                assert got[k]["overlap"] == (ov == "yes")
+                assert got[k]["param_bytes"] == pytest.approx(eval(mem, {}, env) * P)
+                assert got[k]["kv_bytes"] == pytest.approx(eval(kv, {}, env) * KV)
+            others = min(v["comm_elements"] for k, v in got.items() if k != "pipefusion")
+            if N < 2 * L:
+                assert got["pipefusion"]["comm_elements"] < others, (L, N)
+            elif N == 2 * L:
+                assert got["pipefusion"]["comm_elements"] == pytest.approx(others)
+            else:
+                assert got["pipefusion"]["comm_elements"] > others, (L, N)
+
+
 @pytest.mark.parametrize("name", ["K0f", "K1f"])
 def test_cfg_loop_with_one_patch_is_the_exact_guided_sampler(name):
     """M = 1: the guided pipeline equals two full forwards per step combined as eps_u + s (eps_c - eps_u)."""
