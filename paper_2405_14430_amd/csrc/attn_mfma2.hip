@@ -24,6 +24,15 @@
 
 namespace pf {
 
+#ifdef PF_TUNING
+// Timeline probe of a tuning build: shader-clock stamps at the phase boundaries of one outer loop iteration (four tile
+// steps) of every wave of workgroup 0 of the 8-wave kernel, read back with pf_attn_trace_read.
+__device__ unsigned long long g_attn_trace[8][24];
+#define PF_STAMP(slot) do { if (tracing) ts[slot] = clock64(); } while (0)
+#else
+#define PF_STAMP(slot) do { } while (0)
+#endif
+
 namespace {
 
 constexpr int TK = 64;
@@ -200,6 +209,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   for (int j = 0; j < 4; ++j) vaddr[j] = smem + C::K_BYTES + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
 
+#ifdef PF_TUNING
+  unsigned long long ts[24];
+#pragma unroll
+  for (int i = 0; i < 24; ++i) ts[i] = 0;
+  bool tracing = false;
+#endif
   bf16x8 pf[2][2];   // P^T fragments of the tile whose PV product comes next
   f32x16 sacc[2];    // S^T of the tile whose softmax comes next (two blocks of 32 kv rows)
   // The K and V^T fragments of the matrix phases are read from LDS PD instructions ahead of the MFMA that uses them
@@ -379,6 +394,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     // Either way the previous tile's V^T stage stays live one step longer, so the prefetch distance is NS - 2 tiles:
     // at step t the loads of tile t + NS - 2 go into the stage tile t - 2 used.
     static_assert(NW == 4 || NS == 4, "the 8-wave schedule is written for a four-stage ring");
+    // A wave in its matrix phase asks for issue priority over the wave in its vector phase: an MFMA needs the vector
+    // issue port for a few cycles, the arbiter otherwise favours the older wave (waves 0..3) in every conflict, and
+    // waves 4..7 then crawl through their MFMAs while waves 0..3 run their softmax and idle at the barrier afterwards.
+    // (C4 attention 409 -> 400 us, C5 1310 -> 1275 us; priorities 1, 2 and 3 measure the same)
+    constexpr int PRIO_MATRIX = 1;
     const bool late = wave >= 4;
     // (the two schedules are separate loops so that neither pays for the other's live registers)
     // Waves 0..3 load: they wait for their own loads of tile t before the barrier, so that behind the barrier the tile is
@@ -403,12 +423,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     if (!late) {
       auto step = [&](int t, auto stage_c) __attribute__((always_inline)) {
         constexpr int stage = decltype(stage_c)::value;
+        PF_STAMP(stage * 6 + 0);
         top(t, stage_c);
+        PF_STAMP(stage * 6 + 1);
+        __builtin_amdgcn_s_setprio(PRIO_MATRIX);
         if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+        PF_STAMP(stage * 6 + 2);
         scores(stage_c);
+        PF_STAMP(stage * 6 + 3);
+        __builtin_amdgcn_s_setprio(0);
         softmax(t);
+        PF_STAMP(stage * 6 + 4);
       };
       for (int t = t_begin; t < t_end; t += NS) {
+#ifdef PF_TUNING
+        tracing = blockIdx.x == 0 && t == t_begin + 8 * NS;
+#endif
         step(t, std::integral_constant<int, 0>{});
         if (t + 1 < t_end) step(t + 1, std::integral_constant<int, 1>{});
         if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
@@ -418,14 +448,26 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     } else {
       auto step = [&](int t, auto stage_c) __attribute__((always_inline)) {
         constexpr int stage = decltype(stage_c)::value;
+        PF_STAMP(stage * 6 + 0);
         top(t, stage_c);
+        PF_STAMP(stage * 6 + 1);
         if (t > t_begin) {
           softmax(t - 1);
+          PF_STAMP(stage * 6 + 2);
+          __builtin_amdgcn_s_setprio(PRIO_MATRIX);
           pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+        } else {
+          __builtin_amdgcn_s_setprio(PRIO_MATRIX);
         }
+        PF_STAMP(stage * 6 + 3);
         scores(stage_c);
+        PF_STAMP(stage * 6 + 4);
+        __builtin_amdgcn_s_setprio(0);
       };
       for (int t = t_begin; t < t_end; t += NS) {
+#ifdef PF_TUNING
+        tracing = blockIdx.x == 0 && t == t_begin + 8 * NS;
+#endif
         step(t, std::integral_constant<int, 0>{});
         if (t + 1 < t_end) step(t + 1, std::integral_constant<int, 1>{});
         if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
@@ -438,6 +480,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     }
   }
   wait_vmcnt<0>();
+#ifdef PF_TUNING
+  if (NW == 8 && blockIdx.x == 0 && lane == 0) {
+#pragma unroll
+    for (int i = 0; i < 24; ++i) g_attn_trace[wave][i] = ts[i];
+  }
+#endif
 
   // ---- finish
   // O^T row DH sits in block DH / 32 at local row DH % 32 = 8 * (r / 4) + 4 * hi + r % 4: for DH = 72 that is register 4
@@ -498,6 +546,14 @@ hipError_t launch2(const AttnArgs &a, hipStream_t s) {
 }
 
 }  // namespace
+
+#ifdef PF_TUNING
+}  // namespace pf
+extern "C" int pf_attn_trace_read(unsigned long long *out) {   // host array of 8 x 24 stamps
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(pf::g_attn_trace), sizeof(unsigned long long) * 8 * 24);
+}
+namespace pf {
+#endif
 
 bool attn_mfma2_takes_prescaled_q(int head_dim) {
   return (head_dim == 64 || head_dim == 72 || head_dim == 128) && (g_attn_stages == 0 || g_attn_stages == 2);

@@ -9,5 +9,8 @@ extern "C" {
 // the stage's attention launches (600 = heuristic); 700 / 701 / 702: 256-query attention workgroups by launch size /
 // never / always; 800 / 801: folding of the softmax exponent factor into q off / on.
 void pf_tune(int id);
+// Shader-clock stamps of the 8-wave attention kernel's last launch: out[wave][step * 6 + k] for the four tile steps of
+// one outer loop iteration of workgroup 0, k = 0 step entered, 1 behind the barrier, 2 .. 4 phase boundaries.
+int pf_attn_trace_read(unsigned long long *out);
 }
 #endif
