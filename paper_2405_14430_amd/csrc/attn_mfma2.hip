@@ -49,6 +49,49 @@ __device__ __forceinline__ void lds_load16(const void *g, unsigned char *lds_wav
                                    (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, 0);
 }
 
+// LDS fragment reads whose completion is tracked by hand.  The compiler's own wait insertion is of no use in the tile
+// loop: with an LDS-DMA load in flight (there always is one) it treats the LDS counter as unordered and waits for
+// lgkmcnt(0) - every outstanding read - in front of an MFMA instead of for that MFMA's fragment.  The read is issued in
+// inline assembly, address = (base ^ XOR) + OFF with both constants in the instruction stream (no loop-invariant address
+// registers), and lds_wait<N>(frag) waits until at most N LDS operations younger than frag's read are outstanding
+// (LDS returns in order; operations of other kinds in between only make the wait longer).  The fragment passes through
+// the wait as an in/out operand, so its first use cannot be scheduled in front of it.
+template <int XOR, int OFF>
+__device__ __forceinline__ bf16x8 lds_read16_async(unsigned base) {
+  bf16x8 v;
+  static_assert(OFF >= 0, "byte offset");
+  if constexpr (XOR == 0 && OFF <= 65535) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(base), "n"(OFF) : "memory");
+  } else if constexpr (XOR == 0) {
+    unsigned tmp;
+    asm volatile("v_add_u32 %1, %3, %2\n\tds_read_b128 %0, %1" : "=&v"(v), "=&v"(tmp) : "v"(base), "n"(OFF) : "memory");
+  } else if constexpr (OFF <= 65535) {
+    unsigned tmp;
+    asm volatile("v_xor_b32 %1, %3, %2\n\tds_read_b128 %0, %1 offset:%4" : "=&v"(v), "=&v"(tmp) : "v"(base), "n"(XOR), "n"(OFF) : "memory");
+  } else {
+    unsigned tmp;
+    asm volatile("v_xor_b32 %1, %3, %2\n\tv_add_u32 %1, %4, %1\n\tds_read_b128 %0, %1"
+                 : "=&v"(v), "=&v"(tmp) : "v"(base), "n"(XOR), "n"(OFF) : "memory");
+  }
+  return v;
+}
+__device__ __forceinline__ unsigned lds_address(const unsigned char *p) {
+  return (unsigned)(uintptr_t)((const __attribute__((address_space(3))) unsigned char *)p);
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8 &frag) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(N) : "memory");
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void unrolled(F &&f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    unrolled<N, I + 1>(f);
+  }
+}
+
 template <int DH, int NW = 4>
 struct Cfg {
   static constexpr int TQ = 32 * NW;                     // queries per workgroup
@@ -124,8 +167,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   const unsigned char *kh = reinterpret_cast<const unsigned char *>(kbuf + (size_t)h * Lp * DH);
   const bf16_t *vh = vtbuf + (size_t)h * DH * Lp;
 
-  // ---- per-lane source offsets of this wave's load instructions
-  int koff[C::LK];      // byte offset inside a K tile
+  // ---- per-lane source offsets of this wave's load instructions: 32-bit byte offsets from a wave-uniform address, so a
+  // load takes its address as scalar base + one vector register (64-bit per-lane pointers cost the 8-wave kernels
+  // enough registers to spill, and a spill reload inside the tile loop waits for vmcnt(0), i.e. for the prefetched
+  // tiles).  When a wave's instructions are a whole number of swizzle periods apart (LIN: every head size without a
+  // K tail) they differ only by a uniform stride and share one offset register per operand.
+  constexpr bool LIN = !C::TAIL8 && C::K_INSTR % C::NWL == 0 && C::V_INSTR % C::NWL == 0 &&
+                       (C::NWL * 1024) % (16 * C::KROW) == 0;
+  int koff[C::LK];           // byte offset inside a K tile
   unsigned char *kdst[C::LK];
 #pragma unroll
   for (int i = 0; i < C::LK; ++i) {
@@ -135,7 +184,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     koff[i] = r * C::KROW + ((p ^ C::kkey(r)) << 4);
     kdst[i] = smem + ins * 1024;
   }
-  int64_t voff[C::LV];  // element offset inside the head's V^T (without the tile's column offset)
+  int64_t voff[C::LV];       // element offset inside the head's V^T (without the tile's column offset)
   unsigned char *vdst[C::LV];
 #pragma unroll
   for (int i = 0; i < C::LV; ++i) {
@@ -144,13 +193,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     voff[i] = (int64_t)r * Lp + ((p ^ ((r >> 1) & 7)) << 3);
     vdst[i] = smem + C::K_BYTES + ins * 1024;
   }
+  // LIN: the first instruction's offsets as unsigned 32-bit bytes (r < 128 rows of V^T: Lp < 2^23 rows, checked by the host)
+  const unsigned koff0 = (unsigned)koff[0], voff0 = (unsigned)voff[0] * 2u;
+  const size_t vstride = (size_t)C::NWL * 8 * Lp;   // elements between a wave's consecutive V^T instructions (LIN)
   auto issue = [&](int stage, int t) __attribute__((always_inline)) {
     const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
     const bf16_t *vsrc = vh + (size_t)t * TK;
 #pragma unroll
-    for (int i = 0; i < C::LK; ++i) lds_load16(ksrc + koff[i], kdst[i] + stage * C::STAGE);
+    for (int i = 0; i < C::LK; ++i) {
+      if constexpr (LIN) lds_load16(ksrc + (size_t)i * (C::NWL * 1024) + (size_t)koff0, kdst[i] + stage * C::STAGE);
+      else lds_load16(ksrc + koff[i], kdst[i] + stage * C::STAGE);
+    }
 #pragma unroll
-    for (int i = 0; i < C::LV; ++i) lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
+    for (int i = 0; i < C::LV; ++i) {
+      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::STAGE);
+      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
+    }
   };
   // tiles in flight ahead of the one being worked on: NS - 1, or NS - 2 for the 8-wave schedule (see its loop)
   const bool loader = wave < C::NWL;
@@ -199,14 +257,20 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   // Per-lane parts of the LDS addresses, one register per K=16 slice: the row block, the V^T column block and the stage
   // only add constants (a block of 32 rows is a whole number of swizzle periods), which go into the offset field of the
   // LDS reads (where it fits their 16 bits: always with two stages), so a fragment read costs no address arithmetic.
-  const unsigned char *kaddr[C::KS16];
+  // Swizzled head sizes: the K = 16 slice only XORs bits 5.. of the address (below the row stride, above the key's low
+  // bit), so one register per operand serves every slice.  dh = 72 rows (144 B, no swizzle) keep a register per slice.
+  constexpr bool XADDR = !C::TAIL8;
+  unsigned kbase[XADDR ? 1 : C::KS16];
 #pragma unroll
-  for (int ks = 0; ks < C::KS16; ++ks)
-    kaddr[ks] = smem + l32 * C::KROW + ((((hi ^ C::kkey(l32)) << 4)) ^ (ks << 5));
-  const unsigned char *ktail_addr = smem + l32 * C::KROW + C::KS16 * 32 + hi * 8;
-  const unsigned char *vaddr[4];
+  for (int ks = 0; ks < (XADDR ? 1 : C::KS16); ++ks)
+    kbase[ks] = lds_address(smem) + l32 * C::KROW + ((((hi ^ C::kkey(l32)) << 4)) ^ (ks << 5));
+  const unsigned ktail_base = lds_address(smem) + l32 * C::KROW + C::KS16 * 32 + hi * 8;
+  unsigned vbase[XADDR ? 1 : 4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) vaddr[j] = smem + C::K_BYTES + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
+  for (int j = 0; j < (XADDR ? 1 : 4); ++j)
+    vbase[j] = lds_address(smem) + C::K_BYTES + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
+  // stages past the reach of the reads' 16-bit offset field go through a second base (rings of more than 64 KB)
+  const unsigned kbase_hi = kbase[0] + 65536, vbase_hi = vbase[0] + 65536;
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
 
 #ifdef PF_TUNING
@@ -226,29 +290,37 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   auto scores = [&](auto stage_c) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     constexpr int NF = 2 * C::KS16;
-    auto kread = [&](int i) __attribute__((always_inline)) {
-      return *reinterpret_cast<const bf16x8 *>(kaddr[i >> 1] + (stage * C::STAGE + (i & 1) * 32 * C::KROW));
+    auto kread = [&](auto i_c) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_c)::value;
+      constexpr int off = stage * C::STAGE + (i & 1) * 32 * C::KROW;
+      if constexpr (XADDR && off > 65535) return lds_read16_async<((i >> 1) << 5), off - 65536>(kbase_hi);
+      else if constexpr (XADDR) return lds_read16_async<((i >> 1) << 5), off>(kbase[0]);
+      else return lds_read16_async<0, off>(kbase[i >> 1]);
     };
     bf16x8 ring[PD + 1];
-#pragma unroll
-    for (int i = 0; i < PD; ++i) ring[i] = kread(i);
+    unrolled<PD>([&](auto i_c) __attribute__((always_inline)) { ring[decltype(i_c)::value] = kread(i_c); });
     if constexpr (!PRE) {
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[b2][r] = 0.f;
     }
-#pragma unroll
-    for (int i = 0; i < NF; ++i) {
-      if (i + PD < NF) ring[(i + PD) % (PD + 1)] = kread(i + PD);
+    unrolled<NF>([&](auto i_c) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_c)::value;
+      if constexpr (i + PD < NF) {
+        ring[(i + PD) % (PD + 1)] = kread(std::integral_constant<int, i + PD>{});
+        lds_wait<PD>(ring[i % (PD + 1)]);
+      } else {
+        lds_wait<NF - 1 - i>(ring[i % (PD + 1)]);
+      }
       __builtin_amdgcn_sched_barrier(0);
-      const int b2 = i & 1, ks = i >> 1;
+      constexpr int b2 = i & 1, ks = i >> 1;
       sacc[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % (PD + 1)], qf[ks], (PRE && ks == 0) ? cneg : sacc[b2], 0, 0, 0);
-    }
+    });
     if constexpr (C::TAIL8) {
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(ktail_addr + (stage * C::STAGE + b2 * 32 * C::KROW));
+        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(smem + (ktail_base - lds_address(smem)) + (stage * C::STAGE + b2 * 32 * C::KROW));
         sacc[b2] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, kf4),
                                                             __builtin_bit_cast(short4v, qtail), sacc[b2], 0, 0, 0);
       }
@@ -345,19 +417,27 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   auto pv = [&](auto stage_c) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     constexpr int NF = 4 * C::CB;
-    auto vread = [&](int i) __attribute__((always_inline)) {
-      return *reinterpret_cast<const bf16x8 *>(vaddr[i / C::CB] + (stage * C::STAGE + (i % C::CB) * 32 * 128));
+    auto vread = [&](auto i_c) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_c)::value;
+      constexpr int off = stage * C::STAGE + (i % C::CB) * 32 * 128;
+      if constexpr (XADDR && off > 65535) return lds_read16_async<((i / C::CB) << 5), off - 65536>(vbase_hi);
+      else if constexpr (XADDR) return lds_read16_async<((i / C::CB) << 5), off>(vbase[0]);
+      else return lds_read16_async<0, off>(vbase[i / C::CB]);
     };
     bf16x8 ring[PD + 1];
-#pragma unroll
-    for (int i = 0; i < PD; ++i) ring[i] = vread(i);
-#pragma unroll
-    for (int i = 0; i < NF; ++i) {
-      if (i + PD < NF) ring[(i + PD) % (PD + 1)] = vread(i + PD);
+    unrolled<PD>([&](auto i_c) __attribute__((always_inline)) { ring[decltype(i_c)::value] = vread(i_c); });
+    unrolled<NF>([&](auto i_c) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_c)::value;
+      if constexpr (i + PD < NF) {
+        ring[(i + PD) % (PD + 1)] = vread(std::integral_constant<int, i + PD>{});
+        lds_wait<PD>(ring[i % (PD + 1)]);
+      } else {
+        lds_wait<NF - 1 - i>(ring[i % (PD + 1)]);
+      }
       __builtin_amdgcn_sched_barrier(0);
-      const int j = i / C::CB, cb = i % C::CB;
+      constexpr int j = i / C::CB, cb = i % C::CB;
       oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % (PD + 1)], pf[j >> 1][j & 1], oacc[cb], 0, 0, 0);
-    }
+    });
   };
   if constexpr (NW == 4) {
   auto tile_step = [&](int t, auto stage_c) __attribute__((always_inline)) {
@@ -566,7 +646,8 @@ int attn_mfma2_qtile(int nq) {
 }
 
 bool attn_mfma2_supported(const AttnArgs &a) {
-  return (a.head_dim == 64 || a.head_dim == 72 || a.head_dim == 128) && a.rows_padded % TK == 0;
+  // rows_padded < 2^23: the kernel keeps a V^T row offset (up to 127 rows of rows_padded elements) in 32 bits of bytes
+  return (a.head_dim == 64 || a.head_dim == 72 || a.head_dim == 128) && a.rows_padded % TK == 0 && a.rows_padded < (1 << 23);
 }
 
 
