@@ -92,6 +92,16 @@ __device__ __forceinline__ void unrolled(F &&f) {
   }
 }
 
+// Spread of LH load instructions over a matrix phase of NF MFMAs: load j goes in front of MFMA ((2j + 1) NF) / (2 LH).
+// Returns the load that goes in front of MFMA i, or -1.
+constexpr int spread_slot(int i, int NF, int LH) {
+  for (int j = 0; j < LH; ++j)
+    if (((2 * j + 1) * NF) / (2 * LH) == i) return j;
+  return -1;
+}
+static_assert(spread_slot(2, 16, 4) == 0 && spread_slot(14, 16, 4) == 3 && spread_slot(3, 16, 4) == -1, "one load every fourth MFMA");
+static_assert(spread_slot(1, 8, 3) == 0 && spread_slot(4, 8, 3) == 1 && spread_slot(6, 8, 3) == 2, "distinct slots");
+
 template <int DH, int NW = 4>
 struct Cfg {
   static constexpr int TQ = 32 * NW;                     // queries per workgroup
@@ -210,11 +220,51 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
       else lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
     }
   };
-  // tiles in flight ahead of the one being worked on: NS - 1, or NS - 2 for the 8-wave schedule (see its loop)
+  // one of this wave's LPS load instructions of tile t (K instructions first, then V^T)
+  auto issue_one = [&](auto idx_c, int stage, int t) __attribute__((always_inline)) {
+    constexpr int idx = decltype(idx_c)::value;
+    if constexpr (idx < C::LK) {
+      const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
+      if constexpr (LIN) lds_load16(ksrc + (size_t)idx * (C::NWL * 1024) + (size_t)koff0, kdst[idx] + stage * C::STAGE);
+      else lds_load16(ksrc + koff[idx], kdst[idx] + stage * C::STAGE);
+    } else {
+      constexpr int i = idx - C::LK;
+      const bf16_t *vsrc = vh + (size_t)t * TK;
+      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::STAGE);
+      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
+    }
+  };
+  // The 8-wave kernel spreads the LPS loads of the tile it prefetches over the MFMAs of a step's two matrix phases
+  // (half h of the loads inside phase h): issued as one burst behind the barrier they fill the memory pipeline's queue
+  // and hold the loading waves - the critical path of a tile - for some 400 cycles before their first MFMA.
+  constexpr int LH0 = C::LPS / 2, LH1 = C::LPS - LH0;
+  auto spread_load = [&](auto i_c, auto nf_c, auto half_c, int ld_stage, int ld_t) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_c)::value, NF = decltype(nf_c)::value, half = decltype(half_c)::value;
+    if constexpr (half >= 0) {
+      constexpr int LH = half == 0 ? LH0 : LH1;
+      constexpr int j = spread_slot(i, NF, LH);
+      if constexpr (j >= 0) issue_one(std::integral_constant<int, (half == 0 ? 0 : LH0) + j>{}, ld_stage, ld_t);
+    }
+  };
+  auto burst_half = [&](auto half_c, int ld_stage, int ld_t) __attribute__((always_inline)) {
+    constexpr int half = decltype(half_c)::value;
+    unrolled<(half == 0 ? LH0 : LH1)>([&](auto j_c) __attribute__((always_inline)) {
+      issue_one(std::integral_constant<int, (half == 0 ? 0 : LH0) + decltype(j_c)::value>{}, ld_stage, ld_t);
+    });
+  };
+  // tiles in flight ahead of the one being worked on: NS - 1, or NS - 2 for the 8-wave schedule (see its loop), which
+  // always issues NS - 2 tiles (a short split repeats its last tile: its steps count on LPS loads in flight per step)
   const bool loader = wave < C::NWL;
+  if constexpr (NW == 8) {
+    if (loader && t_begin < t_end) {
 #pragma unroll
-  for (int i = 0; i < (NW == 8 ? NS - 2 : NS - 1); ++i)
-    if (loader && t_begin + i < t_end) issue(i, t_begin + i);
+      for (int i = 0; i < NS - 2; ++i) issue(i, min(t_begin + i, t_end - 1));
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+      if (t_begin + i < t_end) issue(i, t_begin + i);
+  }
 
   // ---- Q fragments (B operand): lane holds query q0 + l32, channels ks*16 + 8*hi .. +7
   bf16x8 qf[C::KS16];
@@ -287,7 +337,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   // of every MFMA.
   constexpr int PD = 3;
   // ---- S^T = K . Q^T for the two 32-row blocks of a tile (K from `stage`); consecutive MFMAs alternate between the blocks
-  auto scores = [&](auto stage_c) __attribute__((always_inline)) {
+  auto scores = [&](auto stage_c, auto half_c, int ld_stage, int ld_t) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     constexpr int NF = 2 * C::KS16;
     auto kread = [&](auto i_c) __attribute__((always_inline)) {
@@ -313,6 +363,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
       } else {
         lds_wait<NF - 1 - i>(ring[i % (PD + 1)]);
       }
+      spread_load(i_c, std::integral_constant<int, NF>{}, half_c, ld_stage, ld_t);
       __builtin_amdgcn_sched_barrier(0);
       constexpr int b2 = i & 1, ks = i >> 1;
       sacc[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % (PD + 1)], qf[ks], (PRE && ks == 0) ? cneg : sacc[b2], 0, 0, 0);
@@ -414,7 +465,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   };
   // ---- O^T += V^T . P^T with the V^T tile of `stage` and the fragments softmax left; consecutive MFMAs go to different
   // 32-channel blocks of O^T
-  auto pv = [&](auto stage_c) __attribute__((always_inline)) {
+  auto pv = [&](auto stage_c, auto half_c, int ld_stage, int ld_t) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     constexpr int NF = 4 * C::CB;
     auto vread = [&](auto i_c) __attribute__((always_inline)) {
@@ -434,6 +485,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
       } else {
         lds_wait<NF - 1 - i>(ring[i % (PD + 1)]);
       }
+      spread_load(i_c, std::integral_constant<int, NF>{}, half_c, ld_stage, ld_t);
       __builtin_amdgcn_sched_barrier(0);
       constexpr int j = i / C::CB, cb = i % C::CB;
       oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % (PD + 1)], pf[j >> 1][j & 1], oacc[cb], 0, 0, 0);
@@ -450,9 +502,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     asm volatile("" ::: "memory");
     if (t + NS - 1 < t_end) issue((stage + NS - 1) % NS, t + NS - 1);
 
-    scores(stage_c);
+    scores(stage_c, std::integral_constant<int, -1>{}, 0, 0);
     softmax(t);
-    pv(stage_c);
+    pv(stage_c, std::integral_constant<int, -1>{}, 0, 0);
   };
   for (int t = t_begin; t < t_end; t += NS) {
     tile_step(t, std::integral_constant<int, 0>{});
@@ -482,22 +534,20 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     const bool late = wave >= 4;
     // (the two schedules are separate loops so that neither pays for the other's live registers)
     // Waves 0..3 load: they wait for their own loads of tile t before the barrier, so that behind the barrier the tile is
-    // complete for every wave, and issue the loads of tile t + NS - 2 after it.  Waves 4..7 only meet the barrier.
+    // complete for every wave, and issue the loads of tile t + NS - 2 inside the step's matrix phases.  Waves 4..7 only
+    // meet the barrier.
     auto top = [&](int t, auto stage_c) __attribute__((always_inline)) {
       constexpr int stage = decltype(stage_c)::value;
-      if (!late) {
-        if (t + 1 < t_end) wait_vmcnt<C::LPS>(); else wait_vmcnt<0>();   // tile t landed; tile t + 1 may be in flight
-      }
+      if (!late) wait_vmcnt<C::LPS>();   // tile t landed; the loads of the step before (tile t + 1 or its stand-in) may be in flight
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (!late && t + NS - 2 < t_end) issue((stage + NS - 2) % NS, t + NS - 2);
     };
     auto pv_last = [&]() __attribute__((always_inline)) {
       switch ((t_end - 1 - t_begin) % NS) {
-        case 0: pv(std::integral_constant<int, 0>{}); break;
-        case 1: pv(std::integral_constant<int, 1>{}); break;
-        case 2: pv(std::integral_constant<int, 2>{}); break;
-        default: pv(std::integral_constant<int, 3 % NS>{}); break;
+        case 0: pv(std::integral_constant<int, 0>{}, std::integral_constant<int, -1>{}, 0, 0); break;
+        case 1: pv(std::integral_constant<int, 1>{}, std::integral_constant<int, -1>{}, 0, 0); break;
+        case 2: pv(std::integral_constant<int, 2>{}, std::integral_constant<int, -1>{}, 0, 0); break;
+        default: pv(std::integral_constant<int, 3 % NS>{}, std::integral_constant<int, -1>{}, 0, 0); break;
       }
     };
     if (!late) {
@@ -507,9 +557,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         top(t, stage_c);
         PF_STAMP(stage * 6 + 1);
         __builtin_amdgcn_s_setprio(PRIO_MATRIX);
-        if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+        // prefetch of tile t + NS - 2 (past the end: the last tile again, into a stage nobody reads any more)
+        const int ld_t = min(t + NS - 2, t_end - 1);
+        constexpr int ld_stage = (stage + NS - 2) % NS;
+        constexpr std::integral_constant<int, 0> h0{};
+        constexpr std::integral_constant<int, 1> h1{};
+        if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{}, h0, ld_stage, ld_t);
+        else burst_half(h0, ld_stage, ld_t);
         PF_STAMP(stage * 6 + 2);
-        scores(stage_c);
+        scores(stage_c, h1, ld_stage, ld_t);
         PF_STAMP(stage * 6 + 3);
         __builtin_amdgcn_s_setprio(0);
         softmax(t);
@@ -535,12 +591,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
           softmax(t - 1);
           PF_STAMP(stage * 6 + 2);
           __builtin_amdgcn_s_setprio(PRIO_MATRIX);
-          pv(std::integral_constant<int, (stage + NS - 1) % NS>{});
+          pv(std::integral_constant<int, (stage + NS - 1) % NS>{}, std::integral_constant<int, -1>{}, 0, 0);
         } else {
           __builtin_amdgcn_s_setprio(PRIO_MATRIX);
         }
         PF_STAMP(stage * 6 + 3);
-        scores(stage_c);
+        scores(stage_c, std::integral_constant<int, -1>{}, 0, 0);
         PF_STAMP(stage * 6 + 4);
         __builtin_amdgcn_s_setprio(0);
       };
