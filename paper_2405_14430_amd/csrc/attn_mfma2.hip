@@ -392,7 +392,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[b][r]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));     // both lanes of a query agree
+    {
+      // both lanes of a query agree: the other half-wave's value comes through the vector unit's half-wave swap (an LDS
+      // permute would queue behind the fragment reads of all eight waves and cost the wave an LDS round trip per tile)
+      auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+      tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
     float psum = 0.f;
     unsigned pk[2][8];   // packed bf16 pairs (r, r+1) of the softmax weights
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
