@@ -652,15 +652,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         }
       }
   } else {
-    float *op = ws + ((size_t)sp * nq + qi) * d + (size_t)h * DH;
+    // Partial result of this key split: the normalised output row in fp16 (values of the size of V's, 11 bits against
+    // the 8 the final bf16 output keeps; half the bytes of fp32 numerators, and this traffic is the combine kernel's
+    // whole cost), the reference exponent and the denominator in fp32.  A split that saw no key writes zeros.
+    _Float16 *op = reinterpret_cast<_Float16 *>(ws) + ((size_t)sp * nq + qi) * d + (size_t)h * DH;
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         int c = cb * 32 + 8 * g + 4 * hi;
-        if (c < DH)
-          *reinterpret_cast<float4 *>(op + c) =
-              make_float4(oacc[cb][4 * g], oacc[cb][4 * g + 1], oacc[cb][4 * g + 2], oacc[cb][4 * g + 3]);
+        if (c < DH) {
+          f16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = (_Float16)(oacc[cb][4 * g + e] * inv);
+          *reinterpret_cast<f16x4 *>(op + c) = o4;
+        }
       }
     if (hi == 0) {
       float *ml = ws + (size_t)splits * nq * d + (((size_t)sp * nq + qi) * H + h) * 2;
@@ -704,6 +712,10 @@ bool attn_mfma2_takes_prescaled_q(int head_dim) {
 int attn_mfma2_qtile(int nq) {
   if (g_attn_stages != 0) return 128;                 // the pinned ring depths exist for the 4-wave kernel only
   return g_attn_wide == 2 || (g_attn_wide == 0 && nq >= 1024) ? 256 : 128;
+}
+
+bool attn_partials_half(const AttnArgs &a) {
+  return a.dt == DT_BF16 && a.path != PATH_SIMT && g_attn_variant == 0 && attn_mfma2_supported(a);
 }
 
 bool attn_mfma2_supported(const AttnArgs &a) {

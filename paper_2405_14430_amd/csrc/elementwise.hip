@@ -353,7 +353,9 @@ size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
   return (o + ml) * sizeof(float);
 }
 
-template <typename T>
+// HALF: the partial outputs are normalised rows in fp16 (written by the direct-to-LDS bf16 attention kernel) instead of
+// fp32 numerators; a split's weight then carries its denominator.
+template <typename T, bool HALF = false>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, T *__restrict__ out,
                                                            int64_t ldo, int nq, int H, int dh, int splits, int hpi) {
   // H counts heads over all images of the call (hpi per image); out rows are image-major
@@ -376,7 +378,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     for (int j = 0; j < G; ++j) {
       const int sidx = s0 + j < splits ? s0 + j : splits - 1;
       p[j] = *reinterpret_cast<const float2 *>(ml + (((size_t)sidx * nq + i) * H + h) * 2);
-      v[j] = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
+      if constexpr (HALF) {
+        typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+        const f16x4 hv = *reinterpret_cast<const f16x4 *>(reinterpret_cast<const _Float16 *>(ws) + ((size_t)sidx * nq + i) * d + ch);
+        v[j] = make_float4((float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]);
+      } else {
+        v[j] = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
+      }
     }
     float Mg = M;
 #pragma unroll
@@ -390,8 +398,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const bool live = s0 + j < splits && p[j].y > 0.f;
-      const float wgt = live ? expf(p[j].x - Mg) : 0.f;
-      L += live ? p[j].y * wgt : 0.f;
+      float wgt = live ? expf(p[j].x - Mg) : 0.f;
+      if constexpr (HALF) {   // normalised rows: the weight carries the split's denominator
+        wgt *= live ? p[j].y : 0.f;
+        L += wgt;
+      } else {
+        L += live ? p[j].y * wgt : 0.f;
+      }
       o[0] += live ? v[j].x * wgt : 0.f; o[1] += live ? v[j].y * wgt : 0.f;
       o[2] += live ? v[j].z * wgt : 0.f; o[3] += live ? v[j].w * wgt : 0.f;
     }
@@ -409,7 +422,9 @@ hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s) {
   const int d = a.n_heads * B * a.head_dim;
   int64_t threads = (int64_t)a.nq * (d / 4);
   dim3 g((unsigned)((threads + 255) / 256));
-  if (a.dt == DT_BF16)
+  if (attn_partials_half(a))
+    attn_combine_kernel<bf16_t, true><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
+  else if (a.dt == DT_BF16)
     attn_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
   else
     attn_combine_kernel<float><<<g, 256, 0, s>>>(a.ws, (float *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);

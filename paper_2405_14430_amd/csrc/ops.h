@@ -120,6 +120,7 @@ const char *gemm_mfma_dl_variant_name(const GemmArgs &a);   // kernel instance t
 int gemm_mfma_dl_tile_count();                              // tile configurations the heuristic chooses from
 hipError_t launch_attn_simt(const AttnArgs &a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
+bool attn_partials_half(const AttnArgs &a);               // the launch for `a` leaves normalised fp16 partial outputs
 bool attn_mfma2_supported(const AttnArgs &a);              // direct-to-LDS variant for head sizes 64 / 72 / 128
 hipError_t launch_attn_mfma2(const AttnArgs &a, hipStream_t s);
 int attn_mfma2_qtile(int nq);                              // queries per workgroup it will use for nq query rows per image
