@@ -649,6 +649,10 @@ static int pick_variant(const GemmArgs &a) {
   if (tiles(128, 64) >= 512) return V_128x64;
   const int64_t t64 = tiles(64, 64);
   if (t64 < g_wavek_max_tiles && a.K >= g_wavek_min_k) return V_WAVEK;
+  // one tile per CU at most (the d x d projections of a 512-row patch): the wave-split-K kernel from K = 1024 on
+  // (inside the stage: PixArt-scale cross projections 9.3 -> 8.6 us, SD3-scale out-projection 11.8 -> 10.8 us; with
+  // more tiles than CUs it loses: PixArt-scale QKV 13.2 -> 17.9 us)
+  if (t64 <= 256 && a.K >= 1024) return V_WAVEK;
   if (t64 <= 512) return V_64x64_S4;
   if (t64 <= 768) return V_64x64_S3;
   return V_64x64_S2;
