@@ -362,6 +362,15 @@ pf_status pf_op_gemm_tile(int tile, int dtype, int path, const void *A, int64_t 
                           int gelu_tanh, const float *gate, const float *R, int64_t ldr, void *C2, int64_t ldc2,
                           void *stream);
 
+/*
+ * Host-only view of the bf16 MFMA GEMM's workgroup -> output tile map (for tests of the map; no device work).  A launch
+ * on an M x N output with tile_m x tile_n tiles has *grid workgroups; workgroup ids are dealt round-robin to the 8 XCDs
+ * and every XCD works on one rectangular block of the tile grid.  Returns 1 and the tile indices (row block *tm, column
+ * block *tn) when workgroup `workgroup` computes a tile, 0 when it is one of the surplus ids of the padded grid (or
+ * >= *grid; *tm = *tn = -1), PF_ERR_NULL / PF_ERR_RANGE (negative) on bad arguments.  All pointers are host pointers.
+ */
+int pf_gemm_tile_map(int M, int N, int tile_m, int tile_n, unsigned workgroup, unsigned *grid, int *tm, int *tn);
+
 #ifdef __cplusplus
 }
 #endif

@@ -55,7 +55,7 @@ EXPORTS = ["pf_stage_kv_bytes", "pf_stage_workspace_bytes", "pf_stage_create", "
            "pf_stage_profile",
            "pf_stage_profile_read", "pf_stage_destroy", "pf_status_str", "pf_last_error", "pf_op_modulation",
            "pf_op_ln_modulate", "pf_op_gemm", "pf_op_kv_scatter", "pf_op_attention_ws_bytes", "pf_op_attention", "pf_attention_kernel_name", "pf_probe_mfma_loop",
-           "pf_gemm_tile_count", "pf_op_gemm_tile", "pf_static_scratch_bytes", "pf_op_attention_static", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
+           "pf_gemm_tile_count", "pf_gemm_tile_map", "pf_op_gemm_tile", "pf_static_scratch_bytes", "pf_op_attention_static", "pf_gemm_kernel_name", "pf_op_axpy", "pf_kv_view_image", "pf_op_axpby"]
 
 _lib = None
 
@@ -129,6 +129,8 @@ def load_library():
     lib.pf_op_axpby.argtypes = [vp, vp, f32, f32, vp, i64, vp]
     lib.pf_gemm_tile_count.restype = i32
     lib.pf_gemm_tile_count.argtypes = []
+    lib.pf_gemm_tile_map.restype = i32
+    lib.pf_gemm_tile_map.argtypes = [i32, i32, i32, i32, C.c_uint, C.POINTER(C.c_uint), C.POINTER(i32), C.POINTER(i32)]
     lib.pf_op_gemm_tile.restype = i32
     lib.pf_op_gemm_tile.argtypes = [i32] + lib.pf_op_gemm.argtypes
     _lib = lib

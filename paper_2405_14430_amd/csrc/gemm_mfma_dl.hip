@@ -68,16 +68,18 @@ __device__ __forceinline__ void unrolled(F &&f) {
 // (Flux-scale MLP-down: 623 MB fetched per launch for 157 MB of operands).  Inside the block the N index runs
 // fastest (workgroups in flight together share A tiles; measured equal or better than M fastest on every GEMM of the
 // five workloads, up to 12 % on the QKV projections).  Returns false for the surplus ids of the padded grid.
-__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int gx, int &tm, int &tn) {
+__host__ __device__ __forceinline__ bool tile_of_id(int id, int tiles_m, int tiles_n, int gx, int &tm, int &tn) {
   const int gy = 8 / gx;
   const int bm = (tiles_m + gx - 1) / gx, bn = (tiles_n + gy - 1) / gy;
-  const int id = blockIdx.x;
   const int x = id & 7, j = id >> 3;
   if (j >= bm * bn) return false;
   const int lm = j / bn, ln = j - lm * bn;
   tm = (x % gx) * bm + lm;
   tn = (x / gx) * bn + ln;
   return tm < tiles_m && tn < tiles_n;
+}
+__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int gx, int &tm, int &tn) {
+  return tile_of_id(blockIdx.x, tiles_m, tiles_n, gx, tm, tn);
 }
 
 // Residual and gate operands of a mode-1 epilogue, fetched by the thread that will use them before the K loop starts, so
@@ -563,6 +565,20 @@ int xcd_cut(const GemmArgs &a, int BM, int BN, unsigned *grid) {
   *grid = (unsigned)(8 * bm * bn);
   return best;
 }
+
+}  // namespace
+
+// Host view of the workgroup -> tile map of a launch with BM x BN tiles (what workgroup `id` of the kernel computes):
+// the grid size in *grid, and whether `id` has a tile (then in *tm, *tn).  For the unit test of the map.
+bool gemm_tile_map(int M, int N, int BM, int BN, unsigned id, unsigned *grid, int *tm, int *tn) {
+  GemmArgs a{};
+  a.M = M; a.N = N;
+  const int gx = xcd_cut(a, BM, BN, grid);
+  if (id >= *grid) return false;
+  return tile_of_id((int)id, (M + BM - 1) / BM, (N + BN - 1) / BN, gx, *tm, *tn);
+}
+
+namespace {
 
 bool vec_epilogue_ok(const GemmArgs &a) {
   auto al = [](const void *p, uintptr_t n) { return ((uintptr_t)p % n) == 0; };

@@ -114,6 +114,7 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);   // bytes mu
 // kernel-path specific pieces (defined in gemm_*.hip / attn_*.hip)
 hipError_t launch_gemm_simt(const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);
+bool gemm_tile_map(int M, int N, int BM, int BN, unsigned id, unsigned *grid, int *tm, int *tn);   // host view of the tile map
 bool gemm_mfma_dl_supported(const GemmArgs &a);            // direct-to-LDS multi-stage variant (K % 64 == 0)
 hipError_t launch_gemm_mfma_dl(const GemmArgs &a, hipStream_t s);
 const char *gemm_mfma_dl_variant_name(const GemmArgs &a);   // kernel instance the tile heuristic picks for this shape

@@ -747,6 +747,13 @@ pf_status pf_op_ln_modulate(int dtype, const float *x, int64_t ldx, const float 
   return launch_ln_modulate(dtype, x, ldx, shift, scale, eps, out, ldo, rows, d, normalize, (hipStream_t)stream) == hipSuccess ? PF_OK : PF_ERR_DEVICE;
 }
 
+int pf_gemm_tile_map(int M, int N, int tile_m, int tile_n, unsigned workgroup, unsigned *grid, int *tm, int *tn) {
+  if (!grid || !tm || !tn) return PF_ERR_NULL;
+  if (M < 1 || N < 1 || tile_m < 1 || tile_n < 1) return PF_ERR_RANGE;
+  *tm = *tn = -1;
+  return pf::gemm_tile_map(M, N, tile_m, tile_n, workgroup, grid, tm, tn) ? 1 : 0;
+}
+
 int pf_gemm_tile_count(void) { return gemm_mfma_dl_tile_count(); }
 
 pf_status pf_op_gemm(int dtype, int path, const void *A, int64_t lda, const void *W, int64_t ldw, const void *bias, void *C,

@@ -252,3 +252,52 @@ def test_static_scratch_entry_rejects_oversize_before_touching_the_device(lib):
     assert b"static scratch" in msg and str(cap).encode() in msg
     assert lib.pf_op_attention_static(1, 0, p, 1152, p, p, 0, 4096, 16, 72, p, 1152, 64, 2, None) == -3     # no key rows
     assert lib.pf_op_attention_static(1, 0, None, 1152, p, p, 128, 128, 16, 72, p, 1152, 64, 2, None) == -1
+
+
+def _tile_map(lib, M, N, bm, bn):
+    grid, tm, tn = C.c_uint(0), C.c_int(0), C.c_int(0)
+    assert lib.pf_gemm_tile_map(M, N, bm, bn, 0, C.byref(grid), C.byref(tm), C.byref(tn)) in (0, 1)
+    tiles = {}
+    for wg in range(grid.value):
+        r = lib.pf_gemm_tile_map(M, N, bm, bn, wg, C.byref(grid), C.byref(tm), C.byref(tn))
+        assert r in (0, 1)
+        if r:
+            tiles.setdefault((tm.value, tn.value), []).append(wg)
+    return grid.value, tiles
+
+
+@pytest.mark.parametrize("M,N,bm,bn", [
+    (2048, 9216, 128, 192), (2048, 12288, 256, 192), (2048, 3072, 128, 192),      # Flux-scale projections
+    (4096, 3456, 128, 128), (4096, 1152, 128, 128), (512, 3456, 64, 64), (512, 1152, 64, 64),
+    (666, 4608, 64, 64), (77, 1000, 64, 64), (1, 8, 64, 64), (130, 70, 128, 64), (5000, 40, 256, 256),
+    (64, 100000, 64, 64), (100000, 64, 128, 128)])
+def test_gemm_workgroup_to_tile_map_covers_every_tile_once_and_keeps_an_xcd_in_one_block(lib, M, N, bm, bn):
+    """Host view of the GEMM kernels' workgroup -> tile map: every output tile has exactly one workgroup, the padded
+    grid stays within 9/8 of the tile count plus one row of eight, and the workgroups of one XCD (ids congruent mod 8)
+    cover one rectangle of the tile grid - the point of the map: an XCD's L2 then holds one block's operand panels."""
+    tiles_m, tiles_n = -(-M // bm), -(-N // bn)
+    grid, tiles = _tile_map(lib, M, N, bm, bn)
+    assert sorted(tiles) == [(i, j) for i in range(tiles_m) for j in range(tiles_n)]
+    assert all(len(v) == 1 for v in tiles.values())
+    assert grid % 8 == 0 and grid >= tiles_m * tiles_n
+    for x in range(8):
+        mine = [t for t, wgs in tiles.items() if wgs[0] % 8 == x]
+        if not mine:
+            continue
+        r0, r1 = min(t[0] for t in mine), max(t[0] for t in mine)
+        c0, c1 = min(t[1] for t in mine), max(t[1] for t in mine)
+        assert len(mine) == (r1 - r0 + 1) * (c1 - c0 + 1)          # a full rectangle
+    # past the grid and bad arguments
+    g, a, b = C.c_uint(0), C.c_int(0), C.c_int(0)
+    assert lib.pf_gemm_tile_map(M, N, bm, bn, grid, C.byref(g), C.byref(a), C.byref(b)) == 0 and a.value == -1
+    assert lib.pf_gemm_tile_map(M, N, bm, bn, 0, None, C.byref(a), C.byref(b)) == -1
+    assert lib.pf_gemm_tile_map(0, N, bm, bn, 0, C.byref(g), C.byref(a), C.byref(b)) == -6
+
+
+def test_gemm_tile_map_cuts_the_flux_mlp_down_grid_two_by_four(lib):
+    """2048 x 3072 with 128 x 192 tiles (16 x 16 tiles): the cut with the fewest operand rows per XCD is 2 along M and
+    4 along N (8 x 128 + 4 x 192 = 1792 rows against 2048 for 4 x 2 and 2432 for 1 x 8), without padding."""
+    grid, tiles = _tile_map(lib, 2048, 3072, 128, 192)
+    assert grid == 256
+    mine = sorted(t for t, wgs in tiles.items() if wgs[0] % 8 == 0)
+    assert mine[0] == (0, 0) and mine[-1] == (7, 3) and len(mine) == 32
