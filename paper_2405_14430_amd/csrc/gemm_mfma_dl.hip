@@ -630,8 +630,10 @@ bool gemm_mfma_dl_supported(const GemmArgs &a) { return a.K % BK == 0 && a.K >= 
 //    256x128 runs best with 32-wide K stages and three of them; long-K GEMMs with few tiles (Flux-scale MLP-down:
 //    192 tiles, K = 15360) prefer it too, with 64-wide stages;
 //  * 128x128 (two workgroups per CU) from about 1.5 workgroups per CU, then 128x64;
-//  * skinny GEMMs (n = 512 patch rows): 64x64 tiles with the deepest ring that still lets every workgroup be resident
-//    at once (4 stages: 2 per CU, 3 stages: 3 per CU), and the K-splitting kernel when K is long and tiles are few;
+//  * skinny GEMMs (n = 512 patch rows): 64x64 tiles, four stages while every workgroup is resident at once (two per CU:
+//    up to 512 tiles), two stages (five per CU) beyond - the three-stage ring that used to sit between them lost its
+//    edge once the stage's weights stayed in the memory-side cache (SD3-scale MLP-up, 768 tiles: 21.9 -> 20.9 us) -
+//    and the K-splitting kernel when K is long and tiles are few;
 //  * 192-wide tiles (three 32-column blocks per wave) when they cut the output into a whole number of 256-workgroup
 //    rounds, which power-of-two tiles cannot do for widths that are multiples of 3 * 1024 (Flux-scale stage, patch of
 //    2048 rows: QKV 171 -> 144 us with 768 tiles of 128x192, MLP-up 178 -> 172 us with 512 tiles of 256x192, MLP-down
@@ -670,7 +672,6 @@ static int pick_variant(const GemmArgs &a) {
   // more tiles than CUs it loses: PixArt-scale QKV 13.2 -> 17.9 us)
   if (t64 <= 256 && a.K >= 1024) return V_WAVEK;
   if (t64 <= 512) return V_64x64_S4;
-  if (t64 <= 768) return V_64x64_S3;
   return V_64x64_S2;
 }
 
