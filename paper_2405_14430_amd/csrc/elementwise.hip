@@ -354,36 +354,42 @@ size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
 }
 
 // HALF: the partial outputs are normalised rows in fp16 (written by the direct-to-LDS bf16 attention kernel) instead of
-// fp32 numerators; a split's weight then carries its denominator.
+// fp32 numerators; a split's weight then carries its denominator, and a thread takes eight channels (one 16-byte load per
+// split) instead of four.
 template <typename T, bool HALF = false>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, T *__restrict__ out,
                                                            int64_t ldo, int nq, int H, int dh, int splits, int hpi) {
   // H counts heads over all images of the call (hpi per image); out rows are image-major
+  constexpr int CH = HALF ? 8 : 4;
   const int d = H * dh;
-  const int cpr = d / 4;
+  const int cpr = d / CH;
   int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (id >= (int64_t)nq * cpr) return;
-  int i = (int)(id / cpr), ch = (int)(id % cpr) * 4;
+  int i = (int)(id / cpr), ch = (int)(id % cpr) * CH;
   int h = ch / dh;
   const float *ml = ws + (size_t)splits * nq * d;
   // Eight splits at a time, every load of the group issued before the first use: the loads of one thread are
   // independent, so a group costs one memory latency instead of one per split.  A split that saw no key (l <= 0) may
   // never have written its O rows: its values are dropped by selection, not by a zero weight.
   constexpr int G = 8;
-  float M = -INFINITY, L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+  typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+  float M = -INFINITY, L = 0.f, o[CH];
+#pragma unroll
+  for (int t = 0; t < CH; ++t) o[t] = 0.f;
   for (int s0 = 0; s0 < splits; s0 += G) {
     float2 p[G];
-    float4 v[G];
+    float v[G][CH];
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const int sidx = s0 + j < splits ? s0 + j : splits - 1;
       p[j] = *reinterpret_cast<const float2 *>(ml + (((size_t)sidx * nq + i) * H + h) * 2);
       if constexpr (HALF) {
-        typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-        const f16x4 hv = *reinterpret_cast<const f16x4 *>(reinterpret_cast<const _Float16 *>(ws) + ((size_t)sidx * nq + i) * d + ch);
-        v[j] = make_float4((float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]);
+        const f16x8 hv = *reinterpret_cast<const f16x8 *>(reinterpret_cast<const _Float16 *>(ws) + ((size_t)sidx * nq + i) * d + ch);
+#pragma unroll
+        for (int t = 0; t < CH; ++t) v[j][t] = (float)hv[t];
       } else {
-        v[j] = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
+        const float4 f = *reinterpret_cast<const float4 *>(ws + ((size_t)sidx * nq + i) * d + ch);
+        v[j][0] = f.x; v[j][1] = f.y; v[j][2] = f.z; v[j][3] = f.w;
       }
     }
     float Mg = M;
@@ -394,7 +400,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     const float keep = expf(M - Mg);  // 0 for M = -inf
     L *= keep;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) o[t] *= keep;
+    for (int t = 0; t < CH; ++t) o[t] *= keep;
 #pragma unroll
     for (int j = 0; j < G; ++j) {
       const bool live = s0 + j < splits && p[j].y > 0.f;
@@ -405,8 +411,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
       } else {
         L += live ? p[j].y * wgt : 0.f;
       }
-      o[0] += live ? v[j].x * wgt : 0.f; o[1] += live ? v[j].y * wgt : 0.f;
-      o[2] += live ? v[j].z * wgt : 0.f; o[3] += live ? v[j].w * wgt : 0.f;
+#pragma unroll
+      for (int t = 0; t < CH; ++t) o[t] += live ? v[j][t] * wgt : 0.f;
     }
     M = Mg;
   }
@@ -414,15 +420,16 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
   const int img = h / hpi;
   T *dst = out + ((size_t)img * nq + i) * ldo + (ch - img * hpi * dh);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) Elem<T>::store(dst + t, o[t] * inv);
+  for (int t = 0; t < CH; ++t) Elem<T>::store(dst + t, o[t] * inv);
 }
 
 hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s) {
   const int B = a.batch > 1 ? a.batch : 1;
   const int d = a.n_heads * B * a.head_dim;
-  int64_t threads = (int64_t)a.nq * (d / 4);
+  const bool half = attn_partials_half(a);
+  int64_t threads = (int64_t)a.nq * (d / (half ? 8 : 4));
   dim3 g((unsigned)((threads + 255) / 256));
-  if (attn_partials_half(a))
+  if (half)
     attn_combine_kernel<bf16_t, true><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
   else if (a.dt == DT_BF16)
     attn_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
