@@ -561,8 +561,21 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         default: pv(std::integral_constant<int, 3 % NS>{}, std::integral_constant<int, -1>{}, 0, 0); break;
       }
     };
+    constexpr std::integral_constant<int, 0> S0{};
+    constexpr std::integral_constant<int, 1> S1{};
+    constexpr std::integral_constant<int, 2> S2{};
+    constexpr std::integral_constant<int, 3> S3{};
+    constexpr std::true_type FIRST{};
+    constexpr std::false_type LATER{};
+    // Loop shape, both schedules: the first tile of the split (which has no previous tile to finish) and the up to three
+    // steps that bring the ring back to stage 0 stand in front of the loop, the loop body is four steps without a branch
+    // out of it, and up to three steps follow it.  With exits between the steps of the body the register allocator
+    // placed the O^T accumulators differently in different steps and copied all of them (32 to 40 64-bit moves) once or
+    // twice per loop iteration.  (Only the kernels that take prescaled queries - the ones a stage launches - have that
+    // shape where it fits: with plain queries the dh = 128 kernel would spill under it and keeps the loop with exits.)
+    constexpr bool PEELED = PRE || DH != 128;
     if (!late) {
-      auto step = [&](int t, auto stage_c) __attribute__((always_inline)) {
+      auto step = [&](int t, auto stage_c, auto first_c) __attribute__((always_inline)) {
         constexpr int stage = decltype(stage_c)::value;
         PF_STAMP(stage * 6 + 0);
         top(t, stage_c);
@@ -573,7 +586,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         constexpr int ld_stage = (stage + NS - 2) % NS;
         constexpr std::integral_constant<int, 0> h0{};
         constexpr std::integral_constant<int, 1> h1{};
-        if (t > t_begin) pv(std::integral_constant<int, (stage + NS - 1) % NS>{}, h0, ld_stage, ld_t);
+        if constexpr (!decltype(first_c)::value) pv(std::integral_constant<int, (stage + NS - 1) % NS>{}, h0, ld_stage, ld_t);
         else burst_half(h0, ld_stage, ld_t);
         PF_STAMP(stage * 6 + 2);
         scores(stage_c, h1, ld_stage, ld_t);
@@ -582,23 +595,54 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         softmax(t);
         PF_STAMP(stage * 6 + 4);
       };
-      for (int t = t_begin; t < t_end; t += NS) {
+      if constexpr (!PEELED) {
+        for (int t = t_begin; t < t_end; t += NS) {
+          if (t > t_begin) step(t, S0, LATER);
+          else step(t, S0, FIRST);
+          if (t + 1 < t_end) step(t + 1, S1, LATER);
+          if (t + 2 < t_end) step(t + 2, S2, LATER);
+          if (t + 3 < t_end) step(t + 3, S3, LATER);
+        }
+      } else if (t_begin < t_end) {
+        int t = t_begin;
+        step(t, S0, FIRST); ++t;
+        if (t < t_end) {
+          step(t, S1, LATER); ++t;
+          if (t < t_end) {
+            step(t, S2, LATER); ++t;
+            if (t < t_end) { step(t, S3, LATER); ++t; }
+          }
+        }
+        for (; t + NS <= t_end; t += NS) {
 #ifdef PF_TUNING
-        tracing = blockIdx.x == 0 && t == t_begin + 8 * NS;
+          tracing = blockIdx.x == 0 && t == t_begin + 8 * NS;
 #endif
-        step(t, std::integral_constant<int, 0>{});
-        if (t + 1 < t_end) step(t + 1, std::integral_constant<int, 1>{});
-        if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
-        if (t + 3 < t_end) step(t + 3, std::integral_constant<int, 3>{});
+          step(t, S0, LATER);
+          step(t + 1, S1, LATER);
+          step(t + 2, S2, LATER);
+          step(t + 3, S3, LATER);
+        }
+#ifdef PF_TUNING
+        tracing = false;
+#endif
+        if (t < t_end) {
+          step(t, S0, LATER); ++t;
+          if (t < t_end) {
+            step(t, S1, LATER); ++t;
+            if (t < t_end) step(t, S2, LATER);
+          }
+        }
       }
-      if (t_end > t_begin) pv_last();
+      if (t_begin < t_end) {
+        pv_last();
+      }
     } else {
-      auto step = [&](int t, auto stage_c) __attribute__((always_inline)) {
+      auto step = [&](int t, auto stage_c, auto first_c) __attribute__((always_inline)) {
         constexpr int stage = decltype(stage_c)::value;
         PF_STAMP(stage * 6 + 0);
         top(t, stage_c);
         PF_STAMP(stage * 6 + 1);
-        if (t > t_begin) {
+        if constexpr (!decltype(first_c)::value) {
           softmax(t - 1);
           PF_STAMP(stage * 6 + 2);
           __builtin_amdgcn_s_setprio(PRIO_MATRIX);
@@ -611,16 +655,45 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         PF_STAMP(stage * 6 + 4);
         __builtin_amdgcn_s_setprio(0);
       };
-      for (int t = t_begin; t < t_end; t += NS) {
+      if constexpr (!PEELED) {
+        for (int t = t_begin; t < t_end; t += NS) {
+          if (t > t_begin) step(t, S0, LATER);
+          else step(t, S0, FIRST);
+          if (t + 1 < t_end) step(t + 1, S1, LATER);
+          if (t + 2 < t_end) step(t + 2, S2, LATER);
+          if (t + 3 < t_end) step(t + 3, S3, LATER);
+        }
+      } else if (t_begin < t_end) {
+        int t = t_begin;
+        step(t, S0, FIRST); ++t;
+        if (t < t_end) {
+          step(t, S1, LATER); ++t;
+          if (t < t_end) {
+            step(t, S2, LATER); ++t;
+            if (t < t_end) { step(t, S3, LATER); ++t; }
+          }
+        }
+        for (; t + NS <= t_end; t += NS) {
 #ifdef PF_TUNING
-        tracing = blockIdx.x == 0 && t == t_begin + 8 * NS;
+          tracing = blockIdx.x == 0 && t == t_begin + 8 * NS;
 #endif
-        step(t, std::integral_constant<int, 0>{});
-        if (t + 1 < t_end) step(t + 1, std::integral_constant<int, 1>{});
-        if (t + 2 < t_end) step(t + 2, std::integral_constant<int, 2>{});
-        if (t + 3 < t_end) step(t + 3, std::integral_constant<int, 3>{});
+          step(t, S0, LATER);
+          step(t + 1, S1, LATER);
+          step(t + 2, S2, LATER);
+          step(t + 3, S3, LATER);
+        }
+#ifdef PF_TUNING
+        tracing = false;
+#endif
+        if (t < t_end) {
+          step(t, S0, LATER); ++t;
+          if (t < t_end) {
+            step(t, S1, LATER); ++t;
+            if (t < t_end) step(t, S2, LATER);
+          }
+        }
       }
-      if (t_end > t_begin) {
+      if (t_begin < t_end) {
         softmax(t_end - 1);
         pv_last();
       }
