@@ -151,6 +151,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   using C = Cfg<DH, NW>;
   constexpr int TQ = C::TQ, NT = 64 * NW;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  // LDS ring: the NS K tiles first, then the NS V^T tiles.  Every K fragment then lies within 64 KB of the ring's start
+  // and every V^T fragment within 64 KB of the first V^T tile, the reach of an LDS read's offset field, also in the
+  // 128 KB ring of the 8-wave dh = 128 kernel.
+  constexpr int VRING = NS * C::K_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     for (int e = tid; e < NS * PADB / 16; e += NT) {
       int st = e / (PADB / 16), o = e % (PADB / 16);
       const unsigned fill = (C::ONES_ROW && o < 8) ? 0x3F803F80u : 0u;   // first padding row: bf16 1.0 in every key column
-      *reinterpret_cast<uint4 *>(smem + st * C::STAGE + C::K_BYTES + DH * 128 + o * 16) = make_uint4(fill, fill, fill, fill);
+      *reinterpret_cast<uint4 *>(smem + VRING + st * C::V_BYTES + DH * 128 + o * 16) = make_uint4(fill, fill, fill, fill);
     }
   }
 
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     int ins = min(i * C::NWL + (wave & (C::NWL - 1)), C::V_INSTR - 1);
     int r = ins * 8 + (lane >> 3), p = lane & 7;
     voff[i] = (int64_t)r * Lp + ((p ^ ((r >> 1) & 7)) << 3);
-    vdst[i] = smem + C::K_BYTES + ins * 1024;
+    vdst[i] = smem + VRING + ins * 1024;
   }
   // LIN: the first instruction's offsets as unsigned 32-bit bytes (r < 128 rows of V^T: Lp < 2^23 rows, checked by the host)
   const unsigned koff0 = (unsigned)koff[0], voff0 = (unsigned)voff[0] * 2u;
@@ -217,13 +221,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     const bf16_t *vsrc = vh + (size_t)t * TK;
 #pragma unroll
     for (int i = 0; i < C::LK; ++i) {
-      if constexpr (LIN) lds_load16(ksrc + (size_t)i * (C::NWL * 1024) + (size_t)koff0, kdst[i] + stage * C::STAGE);
-      else lds_load16(ksrc + koff[i], kdst[i] + stage * C::STAGE);
+      if constexpr (LIN) lds_load16(ksrc + (size_t)i * (C::NWL * 1024) + (size_t)koff0, kdst[i] + stage * C::K_BYTES);
+      else lds_load16(ksrc + koff[i], kdst[i] + stage * C::K_BYTES);
     }
 #pragma unroll
     for (int i = 0; i < C::LV; ++i) {
-      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::STAGE);
-      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
+      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::V_BYTES);
+      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::V_BYTES);
     }
   };
   // one of this wave's LPS load instructions of tile t (K instructions first, then V^T)
@@ -231,13 +235,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     constexpr int idx = decltype(idx_c)::value;
     if constexpr (idx < C::LK) {
       const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
-      if constexpr (LIN) lds_load16(ksrc + (size_t)idx * (C::NWL * 1024) + (size_t)koff0, kdst[idx] + stage * C::STAGE);
-      else lds_load16(ksrc + koff[idx], kdst[idx] + stage * C::STAGE);
+      if constexpr (LIN) lds_load16(ksrc + (size_t)idx * (C::NWL * 1024) + (size_t)koff0, kdst[idx] + stage * C::K_BYTES);
+      else lds_load16(ksrc + koff[idx], kdst[idx] + stage * C::K_BYTES);
     } else {
       constexpr int i = idx - C::LK;
       const bf16_t *vsrc = vh + (size_t)t * TK;
-      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::STAGE);
-      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::STAGE);
+      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::V_BYTES);
+      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::V_BYTES);
     }
   };
   // The 8-wave kernel spreads the LPS loads of the tile it prefetches over the MFMAs of a step's two matrix phases
@@ -315,7 +319,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   // LDS reads (where it fits their 16 bits: always with two stages), so a fragment read costs no address arithmetic.
   // Swizzled head sizes: the K = 16 slice only XORs bits 5.. of the address (below the row stride, above the key's low
   // bit), so one register per operand serves every slice.  dh = 72 rows (144 B, no swizzle) keep a register per slice.
-  constexpr bool XADDR = !C::TAIL8;
+  // The 8-wave kernels (two waves per SIMD, one in its matrix phase while the other runs its softmax on the vector unit)
+  // spend the registers instead: a v_xor per fragment read is a vector instruction that the matrix phase takes from the
+  // partner's softmax (26 per tile at dh = 128).
+  constexpr bool XADDR = !C::TAIL8 && NW != 8;
   unsigned kbase[XADDR ? 1 : C::KS16];
 #pragma unroll
   for (int ks = 0; ks < (XADDR ? 1 : C::KS16); ++ks)
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   unsigned vbase[XADDR ? 1 : 4];
 #pragma unroll
   for (int j = 0; j < (XADDR ? 1 : 4); ++j)
-    vbase[j] = lds_address(smem) + C::K_BYTES + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
+    vbase[j] = lds_address(smem) + VRING + l32 * 128 + (((hi ^ ((l32 >> 1) & 7)) << 4) ^ (j << 5));
   // stages past the reach of the reads' 16-bit offset field go through a second base (rings of more than 64 KB)
   const unsigned kbase_hi = kbase[0] + 65536, vbase_hi = vbase[0] + 65536;
   __syncthreads();   // padding rows zeroed (the tile loads in flight do not touch them)
@@ -348,7 +355,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     constexpr int NF = 2 * C::KS16;
     auto kread = [&](auto i_c) __attribute__((always_inline)) {
       constexpr int i = decltype(i_c)::value;
-      constexpr int off = stage * C::STAGE + (i & 1) * 32 * C::KROW;
+      constexpr int off = stage * C::K_BYTES + (i & 1) * 32 * C::KROW;
       if constexpr (XADDR && off > 65535) return lds_read16_async<((i >> 1) << 5), off - 65536>(kbase_hi);
       else if constexpr (XADDR) return lds_read16_async<((i >> 1) << 5), off>(kbase[0]);
       else return lds_read16_async<0, off>(kbase[i >> 1]);
@@ -377,7 +384,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     if constexpr (C::TAIL8) {
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(smem + (ktail_base - lds_address(smem)) + (stage * C::STAGE + b2 * 32 * C::KROW));
+        bf16x4 kf4 = *reinterpret_cast<const bf16x4 *>(smem + (ktail_base - lds_address(smem)) + (stage * C::K_BYTES + b2 * 32 * C::KROW));
         sacc[b2] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, kf4),
                                                             __builtin_bit_cast(short4v, qtail), sacc[b2], 0, 0, 0);
       }
@@ -481,7 +488,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     constexpr int NF = 4 * C::CB;
     auto vread = [&](auto i_c) __attribute__((always_inline)) {
       constexpr int i = decltype(i_c)::value;
-      constexpr int off = stage * C::STAGE + (i % C::CB) * 32 * 128;
+      constexpr int off = stage * C::V_BYTES + (i % C::CB) * 32 * 128;
       if constexpr (XADDR && off > 65535) return lds_read16_async<((i / C::CB) << 5), off - 65536>(vbase_hi);
       else if constexpr (XADDR) return lds_read16_async<((i / C::CB) << 5), off>(vbase[0]);
       else return lds_read16_async<0, off>(vbase[i / C::CB]);
