@@ -64,7 +64,11 @@ typedef enum {
 
 typedef enum {
   PF_PATH_AUTO = 0, /* MFMA kernels for bf16, plain SIMT kernels for fp32 */
-  PF_PATH_SIMT = 1  /* force the plain SIMT kernels (debugging aid; still GPU code) */
+  PF_PATH_SIMT = 1, /* force the plain SIMT kernels (debugging aid; still GPU code) */
+  /* pf_op_attention / pf_op_attention_static only: as PF_PATH_AUTO, but q already carries the factor
+   * log2(e) / sqrt(head_dim), the form in which a stage's QKV projection hands the queries to its self-attention
+   * (the scores are then exponents of 2).  bf16 with head_dim 64, 72 or 128 only: PF_ERR_SHAPE otherwise. */
+  PF_PATH_AUTO_PRESCALED_Q = 2
 } pf_kernel_path;
 
 typedef struct {

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpfstage.so")
 
 PF_F32, PF_BF16 = 0, 1
-PF_PATH_AUTO, PF_PATH_SIMT = 0, 1
+PF_PATH_AUTO, PF_PATH_SIMT, PF_PATH_AUTO_PRESCALED_Q = 0, 1, 2
 KERNEL_CLASSES = ["modulation", "ln_modulate", "gemm_qkv", "kv_scatter", "attention", "attn_combine",
                   "gemm_out", "gemm_xattn", "xattn", "gemm_up", "gemm_down", "copy"]
 STATUS = {0: "PF_OK", -1: "PF_ERR_NULL", -2: "PF_ERR_CONFIG", -3: "PF_ERR_SHAPE", -4: "PF_ERR_DTYPE",

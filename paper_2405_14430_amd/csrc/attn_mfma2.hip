@@ -302,11 +302,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;   // running maximum of the raw scores; per-lane partial sum
   const float sl2 = kLog2e / sqrtf((float)DH);
-  // PRE: probabilities are taken relative to a reference exponent m_ref per query that only moves when a tile's
-  // maximum exceeds it by more than kSlack (and on the first tile): p = 2^(s - m_ref) <= 2^kSlack.  -m_ref is kept
-  // in a 16-register block that seeds the score accumulators (the C operand of a tile's first MFMA), so the
-  // subtraction costs no VALU instruction: the softmax of an element is max, exp2, convert.
-  constexpr float kSlack = 8.f;
+  // PRE: probabilities are taken relative to a reference exponent m_ref per query that only moves on the first tile of
+  // a split and when a later score exceeds the largest one seen at the last move by 8 or more (see softmax):
+  // p = 2^(s - m_ref).  -m_ref is kept in a 16-register block that seeds the score accumulators (the C operand of a
+  // tile's first MFMA), so the subtraction costs no VALU instruction: the softmax of an element is exp2, convert and,
+  // where the denominator is not a row of O^T, one addition.
   float m_ref = 0.f;
   f32x16 cneg;
 #pragma unroll
@@ -400,53 +400,73 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
         for (int r = 0; r < 16; ++r)
           if (jbase + b * 32 + 8 * (r >> 2) + (r & 3) >= kv_rows) sacc[b][r] = -INFINITY;
     }
-    float tmax = sacc[0][0];
+    // maximum of the tile's scores per query (both lanes of a query agree: the other half-wave's value comes through the
+    // vector unit's half-wave swap; an LDS permute would queue behind the fragment reads of all eight waves and cost the
+    // wave an LDS round trip per tile)
+    auto tile_max = [&]() __attribute__((always_inline)) {
+      float m = sacc[0][0];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[b][r]);
-    {
-      // both lanes of a query agree: the other half-wave's value comes through the vector unit's half-wave swap (an LDS
-      // permute would queue behind the fragment reads of all eight waves and cost the wave an LDS round trip per tile)
-      auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
-      tmax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    }
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, sacc[b][r]);
+      auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+      return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    };
     float psum = 0.f;
     unsigned pk[2][8];   // packed bf16 pairs (r, r+1) of the softmax weights
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     if constexpr (PRE) {
+      // The scores arrive relative to the reference (see cneg), so the weights are exp2 of the accumulators as they
+      // are, and the tile's maximum is not needed to form them: it is only computed when the reference has to move,
+      // which the weights themselves tell.  Heads whose denominator comes out of the matrix pipe keep the reference
+      // kRefBias above the largest score seen at its last move and test the exponent's top bit of the packed weights
+      // (a weight of 2 or more, an infinity or a NaN sets it; sixteen words OR-ed three at a time); the others test the
+      // lane's partial sum, which they form anyway.  Either way the reference moves when a score exceeds the largest one
+      // at the last move by 8 or more (up to 13 for the sum test), and on the first tile of a split.
+      constexpr float kRefBias = C::ONES_ROW ? 7.f : 0.f;
+      constexpr float kSumLimit = 8192.f;
       const bool first = t == t_begin;
-      if (first || __builtin_amdgcn_ballot_w64(tmax > kSlack) != 0) {
-        // move the reference: to the tile maximum on the first tile, up by the excess later on
-        const float delta = first ? tmax : fmaxf(tmax, 0.f);
+      bool move = first;
+      for (;;) {
+        if (move) {
+          const float tmax = tile_max();
+          const float delta = first ? tmax + kRefBias : fmaxf(tmax + kRefBias, 0.f);
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[b][r] -= delta;
+          if (!first) {
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
+            l_run *= alpha;
+#pragma unroll
+            for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+          }
+          m_ref += delta;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) cneg[r] = -m_ref;
+        }
+        psum = 0.f;
+        unsigned any = 0;
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[b][r] -= delta;
-        if (!first) {
-          const float alpha = __builtin_amdgcn_exp2f(-delta);
-          l_run *= alpha;
-#pragma unroll
-          for (int cb = 0; cb < C::CB; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
-        }
-        m_ref += delta;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) cneg[r] = -m_ref;
+          for (int r = 0; r < 16; r += 2) {
+            float p0 = __builtin_amdgcn_exp2f(sacc[b][r]);
+            float p1 = __builtin_amdgcn_exp2f(sacc[b][r + 1]);
+            if constexpr (!C::ONES_ROW) psum += p0 + p1;
+            bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
+            pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
+            if constexpr (C::ONES_ROW) any |= pk[b][r >> 1];
+          }
+        const bool bad = C::ONES_ROW ? (any & 0x40004000u) != 0 : !(psum < kSumLimit);
+        if (move || __builtin_amdgcn_ballot_w64(bad) == 0) break;
+        move = true;
       }
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          float p0 = __builtin_amdgcn_exp2f(sacc[b][r]);
-          float p1 = __builtin_amdgcn_exp2f(sacc[b][r + 1]);
-          if constexpr (!C::ONES_ROW) psum += p0 + p1;
-          bf16x2 pp = {(bf16_t)p0, (bf16_t)p1};
-          pk[b][r >> 1] = __builtin_bit_cast(unsigned, pp);
-        }
       if constexpr (!C::ONES_ROW) l_run += psum;
     } else {
+      const float tmax = tile_max();
       const float m_new = fmaxf(m_run, tmax);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
       const float mneg = -m_new * sl2;

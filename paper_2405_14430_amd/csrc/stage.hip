@@ -858,9 +858,13 @@ static pf_status attention_launch(int dtype, int path, const void *q, int64_t ld
                                   int kv_rows, int rows_padded, int n_heads, int head_dim, void *out, int64_t ldo, int nq,
                                   int splits, float *ws, hipStream_t st) {
   AttnArgs a{};
-  a.dt = dtype; a.path = (dtype == PF_BF16 && path == PF_PATH_AUTO) ? PATH_AUTO : PATH_SIMT;
+  const bool prescaled = path == PF_PATH_AUTO_PRESCALED_Q;
+  a.dt = dtype; a.path = (dtype == PF_BF16 && (path == PF_PATH_AUTO || prescaled)) ? PATH_AUTO : PATH_SIMT;
+  a.q_prescaled = prescaled ? 1 : 0;
   a.q = q; a.ldq = ldq; a.kbuf = kbuf; a.vtbuf = vtbuf; a.kv_rows = kv_rows; a.rows_padded = rows_padded; a.n_heads = n_heads;
   a.head_dim = head_dim; a.out = out; a.ldo = ldo; a.nq = nq; a.splits = splits; a.ws = ws;
+  if (prescaled && (dtype != PF_BF16 || !pf::attn_mfma2_takes_prescaled_q(head_dim) || !pf::attn_mfma2_supported(a) || pf::g_attn_variant != 0))
+    return fail(nullptr, PF_ERR_SHAPE, "PF_PATH_AUTO_PRESCALED_Q needs bf16 and head_dim 64, 72 or 128");
   hipError_t e = a.path == PATH_SIMT ? launch_attn_simt(a, st) : launch_attn_bf16(a, st);
   if (e == hipSuccess && splits > 1) e = launch_attn_combine(a, st);
   return e == hipSuccess ? PF_OK : PF_ERR_DEVICE;

@@ -293,6 +293,69 @@ def test_attention_256_query_workgroups(dh, nq, Lkv, splits, gain):
     assert _close(got, po.attention(q, k, v, H), BF, slack=1e-2)
 
 
+@pytest.mark.parametrize("dh", [64, 72, 128])
+@pytest.mark.parametrize("nq,Lkv,splits", [(200, 900, 1), (1100, 1500, 1), (1030, 2100, 3)])
+@pytest.mark.parametrize("pattern", ["random", "rising", "falling", "late_spike", "huge_spike"])
+def test_attention_prescaled_queries_reference_moves(dh, nq, Lkv, splits, pattern):
+    """The kernels a stage launches take queries that already carry log2(e) / sqrt(dh) and form the softmax weights
+    against a reference exponent that only moves when the weights say so.  Score patterns that make it move often
+    (scores rising along the keys), never (falling), once and late (one key far above the rest), and by more than the
+    exponent range of a float (a key whose score is hundreds of powers of two above the first tile's)."""
+    _log("attention prescaled", dh, nq, Lkv, splits, pattern)
+    H = 2
+    rng = _rng(dh * 7919 + nq * 31 + Lkv + len(pattern))
+    q, k, v = _draw(rng, (nq, H * dh), BF), _draw(rng, (Lkv, H * dh), BF), _draw(rng, (Lkv, H * dh), BF)
+    if pattern in ("rising", "falling"):
+        # a common direction u in every head: q.u > 0 for every query, k.u a ramp over the keys
+        u = rng.standard_normal(dh).astype(np.float32)
+        u /= np.linalg.norm(u)
+        ramp = np.linspace(0.0, 6.0, Lkv, dtype=np.float32) * np.sqrt(dh)
+        if pattern == "falling":
+            ramp = ramp[::-1]
+        for h in range(H):
+            k[:, h * dh:(h + 1) * dh] += ramp[:, None] * u[None, :]
+            q[:, h * dh:(h + 1) * dh] += 2.0 * u[None, :]
+        k = wl.round_to_bf16(k)
+        q = wl.round_to_bf16(q)
+    elif pattern in ("late_spike", "huge_spike"):
+        j = Lkv - 70
+        gain = 6.0 if pattern == "late_spike" else 60.0
+        for h in range(H):
+            k[j, h * dh:(h + 1) * dh] = wl.round_to_bf16(gain * np.sign(q[nq // 2, h * dh:(h + 1) * dh]))
+    scale = np.float32(np.log2(np.e) / np.sqrt(dh))
+    qs = wl.round_to_bf16(q * scale)                          # what the kernel receives
+    q_eff = qs.astype(np.float64) / float(scale)              # the queries the kernel then computes with
+    K, Vt, Lp = _kv_buffers(k, v, H, dh, BF)
+    got = _pkg().pf_op_attention(_dev(qs, BF), K, Vt, Lkv, Lp, H, dh, splits=splits, path=_pkg().PF_PATH_AUTO_PRESCALED_Q)
+    torch.cuda.synchronize()
+    name = _pkg().load_library().pf_attention_kernel_name(1, 0, dh, nq, 1).decode()
+    assert name.split("<")[1].split(",")[2] == "true"
+    assert torch.isfinite(got.float()).all()
+    # Bar per element, from the arithmetic: the stored bf16 value is within 2^-9 of what was computed, twice over when
+    # key splits pass through fp16 partial rows (2^-8 |ref| covers both); every softmax weight reaches the matrix unit
+    # rounded to bf16 (2^-9 relative) and the denominator sums the same rounded or unrounded weights, so the weighted
+    # mean moves by at most 2^-8 sum_j p_ij |v_jc| - the attention of |v|, which in the peaked patterns is of the size
+    # of the values, not of the output's rms; 2e-3 rms for the fp32 accumulation.
+    ref = po.attention(q_eff, k, v, H)
+    ref_abs = po.attention(q_eff, k, np.abs(v), H)
+    g = got.double().cpu().numpy()
+    rms = np.sqrt(np.mean(ref ** 2))
+    excess = np.abs(g - ref) / (2.0 ** -8 * np.abs(ref) + 2.0 ** -8 * ref_abs + 2e-3 * rms)
+    _log("  max error / bar", float(excess.max()))
+    assert excess.max() <= 1.0
+
+
+def test_attention_prescaled_path_rejects_other_kernels():
+    pkg = _pkg()
+    q = torch.zeros(8, 80, device="cuda", dtype=BF)
+    K = torch.zeros(2, 128, 40, device="cuda", dtype=BF)
+    Vt = torch.zeros(2, 40, 128, device="cuda", dtype=BF)
+    with pytest.raises(pkg.PfError):
+        pkg.pf_op_attention(q, K, Vt, 100, 128, 2, 40, path=pkg.PF_PATH_AUTO_PRESCALED_Q)      # head size without such a kernel
+    with pytest.raises(pkg.PfError):
+        pkg.pf_op_attention(q.float(), K.float(), Vt.float(), 100, 128, 2, 40, path=pkg.PF_PATH_AUTO_PRESCALED_Q)
+
+
 def test_attention_ignores_finite_padding_rows():
     """Rows beyond kv_rows never contribute, whatever finite values they hold."""
     H, dh, nq, Lkv = 2, 72, 50, 300
