@@ -574,8 +574,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
     // Waves 0..3 load: they wait for their own loads of tile t before the barrier, so that behind the barrier the tile is
     // complete for every wave, and issue the loads of tile t + NS - 2 inside the step's matrix phases.  Waves 4..7 only
     // meet the barrier.
-    auto top = [&](int t, auto stage_c) __attribute__((always_inline)) {
-      constexpr int stage = decltype(stage_c)::value;
+    auto top = [&](int, auto) __attribute__((always_inline)) {
       if (!late) wait_vmcnt<C::LPS>();   // tile t landed; the loads of the step before (tile t + 1 or its stand-in) may be in flight
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
