@@ -50,10 +50,28 @@ __device__ __forceinline__ void wait_vmcnt() {
 // (SD3-scale call 0.357 -> 0.336 ms, PixArt-scale 0.452 -> 0.440 ms; the kernel itself and the Flux-scale call, whose
 // weights do not fit anyway, measure the same).  The workgroups of a head still share its tiles through their XCD's L2.
 constexpr int kTileLoadPolicy = 2;
-__device__ __forceinline__ void lds_load16(const void *g, unsigned char *lds_wave_uniform) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                   (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, 0, kTileLoadPolicy);
-}
+// Tile loads are raw-buffer loads into LDS: a wave-uniform resource over one head's K (or V^T), a wave-uniform byte
+// offset (tile, instruction) and one 32-bit per-lane byte offset, so a load costs no 64-bit per-lane address arithmetic
+// on the vector unit (which a matrix phase would take from the partner wave's softmax).  The resource spans 2 GB from
+// the head's first element; a head's K and V^T are far smaller (the host checks rows_padded < 2^23) and every offset
+// stays inside the head.  The type only exists in device code; the host pass sees a stand-in.
+#if defined(__HIP_DEVICE_COMPILE__)
+struct HeadSource {
+  __amdgpu_buffer_rsrc_t rs;
+  __device__ __forceinline__ explicit HeadSource(const void *base)
+      : rs(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7ffffff0, 0x00020000)) {}
+  // 16 bytes per lane from base + lane_bytes + uniform_bytes to lds_wave_uniform + 16 * lane
+  __device__ __forceinline__ void load16(unsigned lane_bytes, unsigned uniform_bytes, unsigned char *lds_wave_uniform) const {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)lds_wave_uniform, 16, lane_bytes,
+                                             uniform_bytes, 0, kTileLoadPolicy);
+  }
+};
+#else
+struct HeadSource {
+  __device__ explicit HeadSource(const void *) {}
+  __device__ void load16(unsigned, unsigned, unsigned char *) const {}
+};
+#endif
 
 // LDS fragment reads whose completion is tracked by hand.  The compiler's own wait insertion is of no use in the tile
 // loop: with an LDS-DMA load in flight (there always is one) it treats the LDS counter as unordered and waits for
@@ -194,55 +212,49 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   // K tail) they differ only by a uniform stride and share one offset register per operand.
   constexpr bool LIN = !C::TAIL8 && C::K_INSTR % C::NWL == 0 && C::V_INSTR % C::NWL == 0 &&
                        (C::NWL * 1024) % (16 * C::KROW) == 0;
-  int koff[C::LK];           // byte offset inside a K tile
+  unsigned koff[C::LK];      // byte offset inside a K tile
   unsigned char *kdst[C::LK];
 #pragma unroll
   for (int i = 0; i < C::LK; ++i) {
     int ins = min(i * C::NWL + (wave & (C::NWL - 1)), C::K_INSTR - 1);   // surplus slots repeat the last instruction (same data)
     int off = ins * 1024 + lane * 16;
     int r = off / C::KROW, p = (off % C::KROW) >> 4;
-    koff[i] = r * C::KROW + ((p ^ C::kkey(r)) << 4);
+    koff[i] = (unsigned)(r * C::KROW + ((p ^ C::kkey(r)) << 4));
     kdst[i] = smem + ins * 1024;
   }
-  int64_t voff[C::LV];       // element offset inside the head's V^T (without the tile's column offset)
+  unsigned voff[C::LV];      // byte offset inside the head's V^T (without the tile's column offset): row r < 128, Lp < 2^23 rows
   unsigned char *vdst[C::LV];
 #pragma unroll
   for (int i = 0; i < C::LV; ++i) {
     int ins = min(i * C::NWL + (wave & (C::NWL - 1)), C::V_INSTR - 1);
     int r = ins * 8 + (lane >> 3), p = lane & 7;
-    voff[i] = (int64_t)r * Lp + ((p ^ ((r >> 1) & 7)) << 3);
+    voff[i] = ((unsigned)r * (unsigned)Lp + (unsigned)((p ^ ((r >> 1) & 7)) << 3)) * 2u;
     vdst[i] = smem + VRING + ins * 1024;
   }
-  // LIN: the first instruction's offsets as unsigned 32-bit bytes (r < 128 rows of V^T: Lp < 2^23 rows, checked by the host)
-  const unsigned koff0 = (unsigned)koff[0], voff0 = (unsigned)voff[0] * 2u;
-  const size_t vstride = (size_t)C::NWL * 8 * Lp;   // elements between a wave's consecutive V^T instructions (LIN)
+  // LIN: a wave's instructions share the first one's per-lane offsets and differ by a uniform stride
+  const unsigned vstride = (unsigned)C::NWL * 8u * (unsigned)Lp * 2u;   // bytes between a wave's consecutive V^T instructions (LIN)
+  const HeadSource ksrc_h(kh), vsrc_h(vh);
+  auto issue_k = [&](auto i_c, int stage, int t) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_c)::value;
+    const unsigned tile_bytes = (unsigned)t * (unsigned)C::K_BYTES;
+    if constexpr (LIN) ksrc_h.load16(koff[0], tile_bytes + (unsigned)i * (C::NWL * 1024), kdst[i] + stage * C::K_BYTES);
+    else ksrc_h.load16(koff[i], tile_bytes, kdst[i] + stage * C::K_BYTES);
+  };
+  auto issue_v = [&](auto i_c, int stage, int t) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_c)::value;
+    const unsigned tile_bytes = (unsigned)t * (TK * 2u);
+    if constexpr (LIN) vsrc_h.load16(voff[0], tile_bytes + (unsigned)i * vstride, vdst[i] + stage * C::V_BYTES);
+    else vsrc_h.load16(voff[i], tile_bytes, vdst[i] + stage * C::V_BYTES);
+  };
   auto issue = [&](int stage, int t) __attribute__((always_inline)) {
-    const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
-    const bf16_t *vsrc = vh + (size_t)t * TK;
-#pragma unroll
-    for (int i = 0; i < C::LK; ++i) {
-      if constexpr (LIN) lds_load16(ksrc + (size_t)i * (C::NWL * 1024) + (size_t)koff0, kdst[i] + stage * C::K_BYTES);
-      else lds_load16(ksrc + koff[i], kdst[i] + stage * C::K_BYTES);
-    }
-#pragma unroll
-    for (int i = 0; i < C::LV; ++i) {
-      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::V_BYTES);
-      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::V_BYTES);
-    }
+    unrolled<C::LK>([&](auto i_c) __attribute__((always_inline)) { issue_k(i_c, stage, t); });
+    unrolled<C::LV>([&](auto i_c) __attribute__((always_inline)) { issue_v(i_c, stage, t); });
   };
   // one of this wave's LPS load instructions of tile t (K instructions first, then V^T)
   auto issue_one = [&](auto idx_c, int stage, int t) __attribute__((always_inline)) {
     constexpr int idx = decltype(idx_c)::value;
-    if constexpr (idx < C::LK) {
-      const unsigned char *ksrc = kh + (size_t)t * C::K_BYTES;
-      if constexpr (LIN) lds_load16(ksrc + (size_t)idx * (C::NWL * 1024) + (size_t)koff0, kdst[idx] + stage * C::K_BYTES);
-      else lds_load16(ksrc + koff[idx], kdst[idx] + stage * C::K_BYTES);
-    } else {
-      constexpr int i = idx - C::LK;
-      const bf16_t *vsrc = vh + (size_t)t * TK;
-      if constexpr (LIN) lds_load16(reinterpret_cast<const unsigned char *>(vsrc + i * vstride) + (size_t)voff0, vdst[i] + stage * C::V_BYTES);
-      else lds_load16(vsrc + voff[i], vdst[i] + stage * C::V_BYTES);
-    }
+    if constexpr (idx < C::LK) issue_k(idx_c, stage, t);
+    else issue_v(std::integral_constant<int, idx - C::LK>{}, stage, t);
   };
   // The 8-wave kernel spreads the LPS loads of the tile it prefetches over the MFMAs of a step's two matrix phases
   // (half h of the loads inside phase h): issued as one burst behind the barrier they fill the memory pipeline's queue
