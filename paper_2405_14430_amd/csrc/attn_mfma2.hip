@@ -359,8 +359,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   // The K and V^T fragments of the matrix phases are read from LDS PD instructions ahead of the MFMA that uses them
   // (a ring of PD + 1 fragments in registers, the order pinned with scheduling barriers): a wave that is alone in its
   // matrix phase - the other wave of its SIMD being in its softmax - would otherwise wait out an LDS round trip in front
-  // of every MFMA.
-  constexpr int PD = 3;
+  // of every MFMA.  Five ahead in the 8-wave kernels (three: Flux-scale attention 343.6 -> 340.3 us, long-sequence
+  // PixArt 1075 -> 1071 us; two or four ahead measured between).
+  constexpr int PD = NW == 8 ? 5 : 3;
   // ---- S^T = K . Q^T for the two 32-row blocks of a tile (K from `stage`); consecutive MFMAs alternate between the blocks
   auto scores = [&](auto stage_c, auto half_c, int ld_stage, int ld_t) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
