@@ -293,6 +293,20 @@ def test_attention_256_query_workgroups(dh, nq, Lkv, splits, gain):
     assert _close(got, po.attention(q, k, v, H), BF, slack=1e-2)
 
 
+def _attention_error_over_bar(got, q, k, v, H):
+    """Largest element error of a bf16 attention output as a fraction of a bar derived from the arithmetic: the stored
+    bf16 value is within 2^-9 of what was computed, twice over when key splits pass through fp16 partial rows
+    (2^-8 |ref| covers both); every softmax weight reaches the matrix unit rounded to bf16 (2^-9 relative) and the
+    denominator sums the same rounded or unrounded weights, so the weighted mean moves by at most
+    2^-8 sum_j p_ij |v_jc| - the attention of |v|, which for peaked rows is of the size of the values, not of the
+    output's rms; 2e-3 rms for the fp32 accumulation."""
+    ref = po.attention(q, k, v, H)
+    ref_abs = po.attention(q, k, np.abs(v), H)
+    g = got.double().cpu().numpy()
+    rms = np.sqrt(np.mean(ref ** 2))
+    return float((np.abs(g - ref) / (2.0 ** -8 * np.abs(ref) + 2.0 ** -8 * ref_abs + 2e-3 * rms)).max())
+
+
 @pytest.mark.parametrize("dh", [64, 72, 128])
 @pytest.mark.parametrize("nq,Lkv,splits", [(200, 900, 1), (1100, 1500, 1), (1030, 2100, 3)])
 @pytest.mark.parametrize("pattern", ["random", "rising", "falling", "late_spike", "huge_spike"])
@@ -331,18 +345,33 @@ def test_attention_prescaled_queries_reference_moves(dh, nq, Lkv, splits, patter
     name = _pkg().load_library().pf_attention_kernel_name(1, 0, dh, nq, 1).decode()
     assert name.split("<")[1].split(",")[2] == "true"
     assert torch.isfinite(got.float()).all()
-    # Bar per element, from the arithmetic: the stored bf16 value is within 2^-9 of what was computed, twice over when
-    # key splits pass through fp16 partial rows (2^-8 |ref| covers both); every softmax weight reaches the matrix unit
-    # rounded to bf16 (2^-9 relative) and the denominator sums the same rounded or unrounded weights, so the weighted
-    # mean moves by at most 2^-8 sum_j p_ij |v_jc| - the attention of |v|, which in the peaked patterns is of the size
-    # of the values, not of the output's rms; 2e-3 rms for the fp32 accumulation.
-    ref = po.attention(q_eff, k, v, H)
-    ref_abs = po.attention(q_eff, k, np.abs(v), H)
-    g = got.double().cpu().numpy()
-    rms = np.sqrt(np.mean(ref ** 2))
-    excess = np.abs(g - ref) / (2.0 ** -8 * np.abs(ref) + 2.0 ** -8 * ref_abs + 2e-3 * rms)
-    _log("  max error / bar", float(excess.max()))
-    assert excess.max() <= 1.0
+    excess = _attention_error_over_bar(got, q_eff, k, v, H)
+    _log("  max error / bar", excess)
+    assert excess <= 1.0
+
+
+@pytest.mark.parametrize("dh", [64, 72, 128])
+@pytest.mark.parametrize("nq,Lkv,splits", [(1030, 50, 1), (1024, 128, 1), (1100, 190, 1), (1281, 256, 1), (1030, 300, 1),
+                                           (1030, 448, 1), (1100, 1300, 3), (1025, 600, 5)])
+def test_attention_prescaled_queries_short_key_ranges(dh, nq, Lkv, splits):
+    """The 8-wave kernels with prescaled queries keep the first tile of a split, the steps up to the ring's first stage
+    and the last up to three steps outside their tile loop: key ranges of one to seven tiles per split, every residue
+    mod 4, ragged query and key tails, and splits that get no tile at all."""
+    _log("attention prescaled short", dh, nq, Lkv, splits)
+    H = 2
+    rng = _rng(dh * 104729 + nq * 17 + Lkv)
+    q, k, v = _draw(rng, (nq, H * dh), BF, 2.0), _draw(rng, (Lkv, H * dh), BF), _draw(rng, (Lkv, H * dh), BF)
+    scale = np.float32(np.log2(np.e) / np.sqrt(dh))
+    qs = wl.round_to_bf16(q * scale)
+    q_eff = qs.astype(np.float64) / float(scale)
+    K, Vt, Lp = _kv_buffers(k, v, H, dh, BF)
+    got = _pkg().pf_op_attention(_dev(qs, BF), K, Vt, Lkv, Lp, H, dh, splits=splits, path=_pkg().PF_PATH_AUTO_PRESCALED_Q)
+    torch.cuda.synchronize()
+    assert _pkg().load_library().pf_attention_kernel_name(1, 0, dh, nq, 1).decode().split("<")[1].split(",")[3].rstrip(">") == "8"
+    assert torch.isfinite(got.float()).all()
+    excess = _attention_error_over_bar(got, q_eff, k, v, H)
+    _log("  max error / bar", excess)
+    assert excess <= 1.0
 
 
 def test_attention_prescaled_path_rejects_other_kernels():
