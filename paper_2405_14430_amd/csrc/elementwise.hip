@@ -356,7 +356,7 @@ size_t attention_ws_bytes(int nq, int n_heads, int head_dim, int splits) {
 // HALF: the partial outputs are normalised rows in fp16 (written by the direct-to-LDS bf16 attention kernel) instead of
 // fp32 numerators; a split's weight then carries its denominator, and a thread takes eight channels (one 16-byte load per
 // split) instead of four.
-template <typename T, bool HALF = false>
+template <typename T, bool HALF = false, int G = 8>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, T *__restrict__ out,
                                                            int64_t ldo, int nq, int H, int dh, int splits, int hpi) {
   // H counts heads over all images of the call (hpi per image); out rows are image-major
@@ -368,10 +368,10 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
   int i = (int)(id / cpr), ch = (int)(id % cpr) * CH;
   int h = ch / dh;
   const float *ml = ws + (size_t)splits * nq * d;
-  // Eight splits at a time, every load of the group issued before the first use: the loads of one thread are
+  // G splits at a time (eight, or four for launches of at most four splits, whose surplus slots would only repeat the
+  // last split's loads), every load of the group issued before the first use: the loads of one thread are
   // independent, so a group costs one memory latency instead of one per split.  A split that saw no key (l <= 0) may
   // never have written its O rows: its values are dropped by selection, not by a zero weight.
-  constexpr int G = 8;
   typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
   float M = -INFINITY, L = 0.f, o[CH];
 #pragma unroll
@@ -429,7 +429,9 @@ hipError_t launch_attn_combine(const AttnArgs &a, hipStream_t s) {
   const bool half = attn_partials_half(a);
   int64_t threads = (int64_t)a.nq * (d / (half ? 8 : 4));
   dim3 g((unsigned)((threads + 255) / 256));
-  if (half)
+  if (half && a.splits <= 4)
+    attn_combine_kernel<bf16_t, true, 4><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
+  else if (half)
     attn_combine_kernel<bf16_t, true><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
   else if (a.dt == DT_BF16)
     attn_combine_kernel<bf16_t><<<g, 256, 0, s>>>(a.ws, (bf16_t *)a.out, a.ldo, a.nq, a.n_heads * B, a.head_dim, a.splits, a.n_heads);
