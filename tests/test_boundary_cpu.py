@@ -173,6 +173,18 @@ def test_op_argument_checks_without_launching(lib):
     assert lib.pf_op_ln_modulate(0, p, 12, p, p, 1e-6, p, 12, 4, 12, 1, None) == -3
 
 
+def test_prescaled_query_path_is_checked_before_any_launch(lib):
+    text = open(os.path.join(ROOT, "include", "pfstage.h")).read()
+    for name in ("PF_PATH_AUTO", "PF_PATH_SIMT", "PF_PATH_AUTO_PRESCALED_Q"):
+        assert int(re.search(name + r"\s*=\s*(\d+)", text).group(1)) == getattr(B, name)
+    p = C.c_void_p(0x100000)
+    q = B.PF_PATH_AUTO_PRESCALED_Q
+    assert lib.pf_op_attention(0, q, p, 64, p, p, 100, 128, 1, 64, p, 64, 4, 1, None, 0, None) == -3      # fp32 has no such kernel
+    assert lib.pf_op_attention(1, q, p, 40, p, p, 100, 128, 1, 40, p, 40, 4, 1, None, 0, None) == -3      # nor has head size 40
+    assert b"PRESCALED" in lib.pf_last_error(None)
+    assert lib.pf_op_attention_static(1, q, p, 96, p, p, 100, 128, 1, 96, p, 96, 4, 1, None) == -3
+
+
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5", "C3s", "C4s"])
 def test_attention_partials_always_fit_the_reserved_workspace(lib, name):
     """Whatever row count a call has (image-only patch, patch plus joint text rows, warm-up pass, anything
