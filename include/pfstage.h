@@ -321,6 +321,8 @@ pf_status pf_op_kv_scatter(int dtype, void *qkv, int64_t ld, void *kbuf, void *v
  * q dtype [nq, H*dh] (row stride ldq), K [H][rows_padded][dh], V^T [H][dh][rows_padded], out dtype (row
  * stride ldo).  splits >= 1 partitions the key range over workgroups; partial results go through
  * `ws` (float, at least pf_op_attention_ws_bytes bytes; may be NULL when splits == 1 on the SIMT path).
+ * path PF_PATH_AUTO_PRESCALED_Q: q holds q * log2(e) / sqrt(dh) instead of q (same result up to the rounding
+ * of q); a stage config's kernel_path does not take that value (PF_ERR_CONFIG).
  */
 size_t pf_op_attention_ws_bytes(int nq, int n_heads, int head_dim, int splits);
 pf_status pf_op_attention(int dtype, int path, const void *q, int64_t ldq, const void *kbuf,
