@@ -17,13 +17,45 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# Kernels that must not use scratch memory: their LDS fragment reads are asynchronous inline-assembly loads whose
+# completion is tracked by hand, so a register spill between a read and its wait would save a value that has not
+# arrived - wrong results, not just slow ones.  The compiler reports every kernel's scratch size; the build checks it.
+NO_SCRATCH = {"attn_mfma2.hip": "attn_mfma2_kernel"}
+
+
+def _check_no_scratch(src, log):
+    want = NO_SCRATCH.get(src)
+    if not want:
+        return
+    name, seen = None, 0
+    for line in log.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif name and want in name and ("ScratchSize [bytes/lane]:" in line or "VGPRs Spill:" in line):
+            seen += 1
+            if int(line.split(":")[-1].split()[0]) != 0:
+                raise RuntimeError(f"{src}: kernel {name} spills ({line.split('remark:')[-1].strip()}); "
+                                   "its hand-tracked LDS reads are only correct without register spills")
+    if seen == 0:
+        raise RuntimeError(f"{src}: the compiler reported no resource usage for {want}; cannot check for spills")
+
+
 def _compile(src, objdir=OBJ, extra=()):
     obj = os.path.join(objdir, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    check = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
+    cmd = [HIPCC, *FLAGS, *extra, *check, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    out = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)
+    log = r.stdout + r.stderr
+    out = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{out}")
+    if "-DPF_TUNING" in extra:   # the tuning build's timeline stamps cost registers: report, do not refuse
+        try:
+            _check_no_scratch(src, log)
+        except RuntimeError as e:
+            out += f"\nwarning (tuning build): {e}"
+    else:
+        _check_no_scratch(src, log)
     return obj, out
 
 
