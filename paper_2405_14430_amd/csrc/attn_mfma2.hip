@@ -752,9 +752,51 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
   static_assert(!C::ONES_ROW || (DH % 32) == 8, "register index of the ones row is worked out for DH % 32 == 8");
   const float l_tot = C::ONES_ROW ? __shfl(oacc[C::CB - 1][4], l32, kWave) : l_run + __shfl_xor(l_run, 32, kWave);
   const int qi = q0 + l32;
-  if (qi >= nq) return;
   const int d = H * DH;
-  if (splits == 1) {
+  if (splits > 1) {
+    // Partial result of this key split: the normalised output row in fp16 (values of the size of V's, 11 bits against
+    // the 8 the final bf16 output keeps; half the bytes of fp32 numerators, and this traffic is the combine kernel's
+    // whole cost), the reference exponent and the denominator in fp32.  A split that saw no key writes zeros.
+    // The rows go through LDS: in registers a lane holds runs of four channels of its query, which stored directly are
+    // 8-byte pieces 2 d bytes apart (64 addresses per store instruction; with three rounds of workgroups per launch
+    // those stores were 17 us of the Flux-scale launch's 379); staged as [query][channel] rows in the wave's own slice
+    // of the ring, which nobody reads any more, they leave as 16-byte pieces of whole rows.
+    constexpr int ROWB = DH * 2 + 16;                 // bytes per staged row: 16 more than a row, so that rows start 4 banks apart
+    constexpr int CPR = DH * 2 / 16;                  // 16-byte chunks per row
+    static_assert(NW * 32 * ROWB <= NS * C::STAGE, "the staged rows of all waves fit the ring");
+    __syncthreads();                                  // every wave has read its last fragments
+    unsigned char *rows = smem + wave * (32 * ROWB);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int c = cb * 32 + 8 * g + 4 * hi;
+        if (c < DH) {
+          f16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = (_Float16)(oacc[cb][4 * g + e] * inv);
+          *reinterpret_cast<f16x4 *>(rows + l32 * ROWB + c * 2) = o4;
+        }
+      }
+    // (the wave reads back only what it wrote itself: program order within the wave is enough)
+    _Float16 *op0 = reinterpret_cast<_Float16 *>(ws) + ((size_t)sp * nq + q0) * d + (size_t)h * DH;
+#pragma unroll
+    for (int it = 0; it < (32 * CPR + 63) / 64; ++it) {
+      const int idx = it * 64 + lane, r = idx / CPR, ch = idx - r * CPR;
+      if (r < 32 && q0 + r < nq)
+        *reinterpret_cast<uint4 *>(op0 + (size_t)r * d + ch * 8) = *reinterpret_cast<const uint4 *>(rows + r * ROWB + ch * 16);
+    }
+    if (hi == 0 && qi < nq) {
+      float *ml = ws + (size_t)splits * nq * d + (((size_t)sp * nq + qi) * H + h) * 2;
+      ml[0] = (PRE ? m_ref : m_run * sl2) * kLn2;   // natural-log domain reference of the scaled scores, for the combine kernel
+      ml[1] = l_tot;
+    }
+    return;
+  }
+  if (qi >= nq) return;
+  {
     const float inv = 1.f / l_tot;
     bf16_t *op = out + ((size_t)(h / hpi) * nq + qi) * ldo + (size_t)(h % hpi) * DH;
 #pragma unroll
@@ -769,30 +811,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_mfma2_kernel(co
           *reinterpret_cast<bf16x4 *>(op + c) = o4;
         }
       }
-  } else {
-    // Partial result of this key split: the normalised output row in fp16 (values of the size of V's, 11 bits against
-    // the 8 the final bf16 output keeps; half the bytes of fp32 numerators, and this traffic is the combine kernel's
-    // whole cost), the reference exponent and the denominator in fp32.  A split that saw no key writes zeros.
-    _Float16 *op = reinterpret_cast<_Float16 *>(ws) + ((size_t)sp * nq + qi) * d + (size_t)h * DH;
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-#pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        int c = cb * 32 + 8 * g + 4 * hi;
-        if (c < DH) {
-          f16x4 o4;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o4[e] = (_Float16)(oacc[cb][4 * g + e] * inv);
-          *reinterpret_cast<f16x4 *>(op + c) = o4;
-        }
-      }
-    if (hi == 0) {
-      float *ml = ws + (size_t)splits * nq * d + (((size_t)sp * nq + qi) * H + h) * 2;
-      ml[0] = (PRE ? m_ref : m_run * sl2) * kLn2;   // natural-log domain reference of the scaled scores, for the combine kernel
-      ml[1] = l_tot;
-    }
   }
 }
 
