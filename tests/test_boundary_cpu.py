@@ -313,3 +313,18 @@ def test_gemm_tile_map_cuts_the_flux_mlp_down_grid_two_by_four(lib):
     assert grid == 256
     mine = sorted(t for t, wgs in tiles.items() if wgs[0] % 8 == 0)
     assert mine[0] == (0, 0) and mine[-1] == (7, 3) and len(mine) == 32
+
+
+def test_build_refuses_an_attention_kernel_that_spills():
+    """The attention kernels' LDS fragment reads are asynchronous loads tracked by hand, so a register spill makes them
+    wrong, not slow: the build reads the compiler's per-kernel resource remarks and refuses scratch use."""
+    from paper_2405_14430_amd import build as bld
+    def log(scratch, spill):
+        return ("a.hip:1:1: remark: Function Name: _ZN2pf17attn_mfma2_kernelILi128EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+                f"a.hip:1:1: remark:     ScratchSize [bytes/lane]: {scratch} [-Rpass-analysis=kernel-resource-usage]\n"
+                f"a.hip:1:1: remark:     VGPRs Spill: {spill} [-Rpass-analysis=kernel-resource-usage]\n")
+    bld._check_no_scratch("attn_mfma2.hip", log(0, 0))
+    bld._check_no_scratch("gemm_mfma_dl.hip", log(64, 3))          # not a checked source
+    for bad in (log(24, 0), log(0, 2), "no remarks at all"):
+        with pytest.raises(RuntimeError):
+            bld._check_no_scratch("attn_mfma2.hip", bad)
